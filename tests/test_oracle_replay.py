@@ -1,0 +1,131 @@
+"""Invariants of the method, checked on the oracle's replay of operation traces: shared
+prefix == isolated per-task copies, the action expert's view never sees language appends,
+batch independence, frame-chop invariance, placement independence.  No GPU."""
+import numpy as np
+
+from oracle import attention
+from oracle.pool_model import ACTION, DECODE
+from oracle.replay import OracleWorld
+from paper_2603_14371_amd import synth
+
+
+def _replay(w, layers=None, free_order="workload", head_dim=None):
+    src = synth.DataSource(w["seed"], w["sigma"], head_dim=head_dim or w["head_dim"])
+    order = w["free_order"] if isinstance(free_order, str) else free_order
+    world = OracleWorld(w["num_blocks"], w["n_layers"], src, w["scale"],
+                        free_order=None if order is None else list(order), layers=layers)
+    return world, world.run(w["trace"])
+
+
+def test_shared_prefix_equals_isolated_recomputation():
+    """Paper Sec. 1 / Sec. 3.2: one prefill fanned out to all tasks gives what each task would
+    get from its own prefill of the same observation."""
+    kw = dict(n_layers=2, prefix_len=40, chunk=6, denoise_steps=3, decode_targets=(4, 7, 9))
+    shared, iso = synth.cross_task(**kw), synth.cross_task(isolated=True, **kw)
+    _, rs = _replay(shared, head_dim=32)
+    _, ri = _replay(iso, head_dim=32)
+    steps_s = [(op, r) for op, r in zip(shared["trace"], rs) if op["op"] == "step"]
+    steps_i = [(op, r) for op, r in zip(iso["trace"], ri) if op["op"] == "step"]
+    n_checked = 0
+    for op, r in steps_s:
+        mine = [(o, x) for o, x in steps_i if o["shared_step"] == op["shared_step"]]
+        assert [it for o, _ in mine for it in o["items"]] == op["items"]
+        for layer in (0, 1):
+            cat = np.concatenate([x["O"][layer] for _, x in mine])
+            assert np.array_equal(cat, r["O"][layer])       # the oracle: exactly equal
+            n_checked += 1
+    assert n_checked == 2 * 9
+    # and the isolated pool holds four copies of the prefix
+    assert sum(1 for op in iso["trace"] if op["op"] == "prefix_create") == 4
+
+
+def _mini_world(data, n_layers=1):
+    return OracleWorld(64, n_layers, data, 0.25, page_size=16)
+
+
+def test_action_view_is_independent_of_language_appends_and_of_batch_mates():
+    """Sec. 1 (heterogeneous KV semantics) and App. A.2 (pure batching): the action chunk's
+    output is the same whether or not a decode stream on the same prefix has appended, and
+    an item's output does not depend on what else is in the batch or on item order."""
+    data = synth.DataSource(77, head_dim=32)
+    chunk_recipe = {"tag": 500, "tok0": 0, "n_total": 5}
+
+    def run(with_decode, decode_first):
+        w = _mini_world(data)
+        w.apply({"op": "prefix_create"})
+        w.apply({"op": "prefix_append", "pid": 0, "n": 20, "pos0": 0,
+                 "data": {"tag": 1, "tok0": 0, "n_total": 20}})
+        a = w.apply({"op": "stream_create", "pid": 0, "kind": ACTION})["sid"]
+        d = w.apply({"op": "stream_create", "pid": 0, "kind": DECODE})["sid"]
+        if with_decode:
+            w.apply({"op": "step", "items": [(d, 9)], "attend": False,
+                     "data": {"tag": 2, "tok0": 0, "n_total": 9}})
+        if not with_decode:
+            return w.apply({"op": "step", "items": [(a, 5)], "data": chunk_recipe})["O"][0]
+        # action rows must come from the same recipe rows: put them first or last
+        if decode_first:
+            rec = {"tag": 501, "tok0": 0, "n_total": 6}
+            o = w.apply({"op": "step", "items": [(d, 1), (a, 5)], "data": rec})["O"][0]
+            return o[1:], rec
+        rec = {"tag": 501, "tok0": 0, "n_total": 6}
+        o = w.apply({"op": "step", "items": [(a, 5), (d, 1)], "data": rec})["O"][0]
+        return o[:5], rec
+
+    alone = run(False, False)
+    # same q bits for the chunk are needed to compare: rebuild with explicit arrays instead
+    q = data(chunk_recipe, 0, "q", 5)
+    kp, vp = data({"tag": 1, "tok0": 0, "n_total": 20}, 0, "k", 20), \
+        data({"tag": 1, "tok0": 0, "n_total": 20}, 0, "v", 20)
+    ko, vo = data(chunk_recipe, 0, "k", 5), data(chunk_recipe, 0, "v", 5)
+    direct, _ = attention.attend_item(ACTION, q, kp, vp, ko, vo, 0.25)
+    assert np.array_equal(alone, direct)
+    # in a mixed batch (different recipe -> different bits) only the *structure* can be
+    # compared: recompute directly from that batch's bits and demand equality
+    for decode_first in (False, True):
+        o, rec = run(True, decode_first)
+        t0 = 1 if decode_first else 0
+        qm = data(rec, 0, "q", 6)[t0:t0 + 5]
+        km, vm = data(rec, 0, "k", 6)[t0:t0 + 5], data(rec, 0, "v", 6)[t0:t0 + 5]
+        direct, _ = attention.attend_item(ACTION, qm, kp, vp, km, vm, 0.25)
+        assert np.array_equal(o, direct)
+
+
+def test_frame_chop_invariance_and_resume():
+    """Sec. 3.2 / App. A.2: a request interrupted every k tokens and resumed next frame
+    yields what uninterrupted decoding yields; its earlier blocks never move."""
+    data = synth.DataSource(78, head_dim=32)
+    outs = {}
+    tables = {}
+    for k in (1, 3, 12):
+        w = _mini_world(data)
+        w.apply({"op": "prefix_create"})
+        w.apply({"op": "prefix_append", "pid": 0, "n": 18, "pos0": 0,
+                 "data": {"tag": 1, "tok0": 0, "n_total": 18}})
+        d = w.apply({"op": "stream_create", "pid": 0, "kind": DECODE})["sid"]
+        got = []
+        seen_blocks = []
+        for j in range(12):
+            if j % k == 0 and j > 0:
+                # frame boundary: other traffic allocates and frees blocks in between
+                other = w.apply({"op": "stream_create", "pid": -1, "kind": DECODE})["sid"]
+                w.apply({"op": "step", "items": [(other, 20)], "attend": False,
+                         "data": {"tag": 900 + j, "tok0": 0, "n_total": 20}})
+                w.apply({"op": "stream_release", "sid": other})
+            r = w.apply({"op": "step", "items": [(d, 1)],
+                         "data": {"tag": 100 + j, "tok0": 0, "n_total": 1}})
+            got.append(r["O"][0][0])
+            blocks = list(w.pool.streams[d].blocks)
+            assert blocks[:len(seen_blocks)] == seen_blocks
+            seen_blocks = blocks
+        outs[k] = np.stack(got)
+        tables[k] = seen_blocks
+    assert np.array_equal(outs[1], outs[3]) and np.array_equal(outs[1], outs[12])
+
+
+def test_outputs_do_not_depend_on_block_placement_but_tables_do():
+    w = synth.tiny()
+    w1, r1 = _replay(w, head_dim=32)
+    w2, r2 = _replay(w, free_order=list(range(w["num_blocks"]))[::-1], head_dim=32)
+    assert np.array_equal(r1[-1]["O"][0], r2[-1]["O"][0])
+    assert r1[-1]["slots"] != r2[-1]["slots"]
+    assert r1[-1]["O"][0].shape == (11, 8, 32)
