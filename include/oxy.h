@@ -1,0 +1,200 @@
+/* oxy.h -- C ABI of the mixed action+decode attention step over a shared, paged,
+ * refcounted prefix KV cache (MI355X / gfx950).
+ *
+ * The paper's unified KV cache manager (Sec. 3.2; App. A.2) keeps one resumable
+ * state per request, sigma = (KV cache, token buffer, termination flag), and
+ * offers Store / Retrieve / Update / Remove plus Batch / UnBatch.  This library
+ * is the KV part of that manager and the attention that reads it:
+ *
+ *   prefill cache K_t of a frame (Eq. 1)        -> a *prefix*: refcounted blocks, read-only
+ *                                                  once anything is attached to it
+ *   fan-out to action and language expert        -> *streams* attached to one prefix
+ *   Store / Remove                               -> oxy_stream_create / oxy_stream_release
+ *   Retrieve + Batch (Alg. 1, second stage)      -> oxy_batch_build (zero-copy: a descriptor
+ *                                                  of block tables, no stacking of tensors)
+ *   Update (KV grows by the decoded tokens)      -> oxy_batch_build (lengths, blocks) +
+ *                                                  oxy_stream_append (the K/V rows)
+ *   the attention of ActionDenoise / BatchedLanguageDecode (Eq. 5, Eq. 6)
+ *                                                -> oxy_mixed_attention, one launch for
+ *                                                  action-chunk and decode queries together
+ *   UnBatch                                      -> nothing to do: block tables persist
+ *
+ * Geometry is fixed to the attention shape the kernels are written for:
+ * 8 query heads sharing 1 KV head, head_dim 256, page size 16 tokens, bf16.
+ *
+ * Conventions
+ *  - Every call returns 0 (OXY_OK) or a negative oxy_status; no C++ exception
+ *    crosses this boundary.  oxy_last_error() gives a thread-local message.
+ *  - A failing call changes no pool state (OXY_ERR_NO_BLOCKS is detected before
+ *    any block is taken).
+ *  - Pointers marked DEVICE are device memory owned by the caller; pointers
+ *    marked HOST are host memory owned by the caller.  The library owns only its
+ *    host metadata and a small pinned staging buffer per live batch.
+ *  - All device work is enqueued on the caller's hipStream_t (passed as void*);
+ *    no call synchronises the device.  Calls that touch the same batch, or that
+ *    free and re-use blocks, must be ordered on one HIP stream by the caller.
+ *  - Ids are sequential from 0 and never reused (App. A.2: the id of a request
+ *    is the number of requests created before it); prefixes and streams count
+ *    separately.
+ *  - Not thread-safe per pool: one host thread drives one pool.
+ *
+ * Block pool policy (the paper has no allocator; this is the specification the
+ * block tables are tested against, bit for bit): LIFO free stack whose initial
+ * order is `free_order` (first element popped first; default 0,1,2,...); blocks
+ * are popped one at a time in logical order, items of a batch in batch order;
+ * release subtracts one reference per table entry and pushes, in ascending
+ * logical order, the blocks that reach zero -- a stream's own table first, then
+ * the table of the prefix it was attached to.
+ *
+ * Device layout of the KV buffer (private to the library, stated for the record):
+ * layer l starts at l * num_blocks * 16 KiB; block b of a layer is 16 KiB: the
+ * K page (8 KiB) then the V page (8 KiB).  Pages are stored in the operand
+ * order of the 16x16x32 bf16 MFMA so that one wavefront-wide 16-byte-per-lane
+ * load is one contiguous KiB:
+ *   K page: 16-byte chunk (j, g, key), j<8, g<4, key<16, at byte ((j*4+g)*16+key)*16
+ *           holds K[key][32j+8g .. 32j+8g+7].
+ *   V page: 16-byte chunk (c, g, m), c<8, g<4, m<16, at byte ((c*4+g)*16+m)*16
+ *           holds V[4g..4g+3][32c+m] followed by V[4g..4g+3][32c+16+m].
+ * oxy_gather_kv reads tokens back in the natural [token][256] order.
+ */
+#ifndef OXY_H
+#define OXY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OXY_OK = 0,
+  OXY_ERR_INVALID_ARG = -1, /* null pointer, size out of range, duplicate stream in a batch   */
+  OXY_ERR_NO_BLOCKS = -2,   /* not enough free blocks; nothing was allocated                   */
+  OXY_ERR_BAD_ID = -3,      /* unknown, released, or no longer attachable id                   */
+  OXY_ERR_SEALED = -4,      /* append to a prefix that already has a stream attached           */
+  OXY_ERR_BUSY = -5,        /* too many live batches, or pool destroyed with live batches      */
+  OXY_ERR_WORKSPACE = -6,   /* batch does not fit the workspace the pool was created with      */
+  OXY_ERR_DEVICE = -7       /* a HIP call failed; message holds hipGetErrorString              */
+} oxy_status;
+
+enum { OXY_KIND_ACTION = 0, OXY_KIND_DECODE = 1 };
+
+/* pool flags */
+enum { OXY_POOL_HOST_ONLY = 1 }; /* metadata only: no device pointer is touched, no HIP call is
+                                    made; append/attention/gather return OXY_ERR_INVALID_ARG.
+                                    For indexing tests on machines without a GPU.              */
+/* batch flags */
+enum { OXY_BATCH_APPEND_ONLY = 1 }; /* lengths, blocks and slots only; no attention work list
+                                       (used to load a history); oxy_mixed_attention on such a
+                                       batch returns OXY_ERR_INVALID_ARG                        */
+
+typedef struct oxy_pool oxy_pool;   /* opaque host object                                   */
+typedef struct oxy_batch oxy_batch; /* opaque; one step's descriptor (Alg. 1: the batched
+                                       state, here block tables instead of stacked tensors) */
+
+typedef struct {
+  int32_t n_layers;         /* L >= 1                                                        */
+  int32_t n_q_heads;        /* must be 8                                                     */
+  int32_t n_kv_heads;       /* must be 1                                                     */
+  int32_t head_dim;         /* must be 256                                                   */
+  int32_t page_size;        /* must be 16                                                    */
+  int32_t num_blocks;       /* capacity in blocks (one block = 16 tokens in every layer)     */
+  void *kv_base;            /* DEVICE, >= oxy_kv_bytes(), 256-byte aligned                   */
+  size_t kv_bytes;
+  void *workspace;          /* DEVICE, >= oxy_workspace_bytes(), 256-byte aligned            */
+  size_t workspace_bytes;
+  const int32_t *free_order;/* HOST, optional permutation of [0,num_blocks); copied          */
+  int32_t max_live_batches; /* descriptors that may exist at once (0 -> 2)                   */
+  int32_t max_q_tokens;     /* query tokens per attended batch (0 -> 1024)                   */
+  int32_t max_append_tokens;/* new tokens per batch, append-only ones included (0 -> 16*num_blocks) */
+  int32_t max_work_items;   /* attention work items per batch (0 -> 16384)                   */
+  int32_t max_partials;     /* per-token split results per batch (0 -> 32*max_q_tokens)      */
+  int32_t split_tokens;     /* KV tokens per work item, multiple of 32 (0 -> 256).  Fixed per
+                               pool so an item's arithmetic never depends on its batch mates */
+  int32_t flags;
+} oxy_pool_config;
+
+typedef struct {
+  int32_t stream_id;
+  int32_t n_new; /* >= 1 tokens appended AND queried this step.  ACTION streams are rewound
+                    to length 0 first: the chunk's K/V is transient per denoising step      */
+} oxy_item;
+
+/* sizes the caller must provide for kv_base / workspace (0 on invalid config) */
+size_t oxy_kv_bytes(const oxy_pool_config *cfg);
+size_t oxy_workspace_bytes(const oxy_pool_config *cfg);
+
+/* Creates the host metadata; the KV buffer is not initialised (stale contents are never
+ * read: keys beyond a length are masked and their values zero-selected). */
+int32_t oxy_pool_create(const oxy_pool_config *cfg, oxy_pool **out);
+int32_t oxy_pool_destroy(oxy_pool *pool); /* BUSY if batches are still alive */
+
+/* --- prefix = prefill cache K_t of one observation (Sec. 3.1, Eq. 1) ------------------- */
+int32_t oxy_prefix_create(oxy_pool *pool, int32_t *prefix_id); /* holds the creator's reference */
+/* Writes tokens [pos0, pos0+n_tokens) of one layer.  k, v: DEVICE bf16 [n_tokens][256].
+ * pos0 <= current length (no holes).  Blocks are taken the first time a token range is
+ * reached (by whichever layer comes first).  SEALED once a stream is attached. */
+int32_t oxy_prefix_append(oxy_pool *pool, int32_t prefix_id, int32_t layer, const void *k,
+                          const void *v, int32_t n_tokens, int32_t pos0, void *hip_stream);
+/* Drops the creator's reference; attached streams keep the blocks alive (a request carried
+ * over to later frames keeps the prefill cache of its birth frame, Sec. 3.2). */
+int32_t oxy_prefix_release(oxy_pool *pool, int32_t prefix_id);
+
+/* --- stream = KV part of one request state (Sec. 3.2, Eq. 3; App. A.2 Store/Remove) ---- */
+int32_t oxy_stream_create(oxy_pool *pool, int32_t prefix_id /* -1: none */, int32_t kind,
+                          int32_t *stream_id);
+int32_t oxy_stream_release(oxy_pool *pool, int32_t stream_id);
+int32_t oxy_stream_rewind(oxy_pool *pool, int32_t stream_id, int32_t new_len); /* keeps blocks */
+
+/* --- one step (Alg. 1: Retrieve + Batch; App. A.2 Update) ------------------------------ */
+/* items: HOST.  Extends every listed stream by n_new tokens (taking blocks as needed), records
+ * the slot of every new token, builds the attention work list and uploads the descriptor on
+ * hip_stream.  The descriptor serves every layer of the step. */
+int32_t oxy_batch_build(oxy_pool *pool, const oxy_item *items, int32_t n_items, int32_t flags,
+                        void *hip_stream, oxy_batch **out);
+/* k_new, v_new: DEVICE bf16 [sum n_new][256], items in batch order.  Scatters them into the
+ * slots of `layer`. */
+int32_t oxy_stream_append(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
+                          const void *k_new, const void *v_new, void *hip_stream);
+/* q: DEVICE bf16 [sum n_new][8][256]; out: DEVICE bf16, same shape; lse: DEVICE float
+ * [sum n_new][8] or NULL (natural-log sum of exp of the scaled logits over the visible set).
+ * Visible set of a query (Eq. 2, Eq. 5, Eq. 6): the whole prefix of its stream, plus
+ *   ACTION: every own token of the chunk (bidirectional);
+ *   DECODE: own tokens 0..p where p is the query's own position (causal, itself included).
+ * Must be enqueued after oxy_stream_append of the same layer on the same stream. */
+int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
+                            const void *q, void *out, float *lse, float scale,
+                            void *hip_stream);
+int32_t oxy_batch_destroy(oxy_batch *batch);
+
+/* Reads K/V rows back in natural order: slots HOST int64 [n] (block*16+offset);
+ * k_out, v_out: DEVICE bf16 [n][256]. */
+int32_t oxy_gather_kv(oxy_pool *pool, int32_t layer, const int64_t *slots, int32_t n,
+                      void *k_out, void *v_out, void *hip_stream);
+
+/* --- introspection (HOST outputs; these are the indexing results compared bit-exactly) -- */
+int32_t oxy_stream_info(oxy_pool *pool, int32_t stream_id, int32_t *prefix_id, int32_t *kind,
+                        int32_t *own_len, int32_t *n_blocks);
+int32_t oxy_stream_blocks(oxy_pool *pool, int32_t stream_id, int32_t *out, int32_t cap);
+int32_t oxy_prefix_info(oxy_pool *pool, int32_t prefix_id, int32_t *len, int32_t *n_blocks,
+                        int32_t *sealed, int32_t *n_streams);
+int32_t oxy_prefix_blocks(oxy_pool *pool, int32_t prefix_id, int32_t *out, int32_t cap);
+int32_t oxy_block_refcounts(oxy_pool *pool, int32_t *out, int32_t cap); /* cap >= num_blocks */
+int32_t oxy_free_blocks(oxy_pool *pool, int32_t *out, int32_t cap);     /* top of stack first */
+int32_t oxy_pool_stats(oxy_pool *pool, int32_t *free_blocks, int32_t *live_prefixes,
+                       int32_t *live_streams);
+int32_t oxy_batch_info(const oxy_batch *batch, int32_t *n_items, int32_t *n_tokens,
+                       int32_t *n_work, int32_t *n_partials);
+int32_t oxy_batch_slots(const oxy_batch *batch, int64_t *out, int32_t cap);
+/* Raw work list, 8 int32 per item: token-list offset, token count, block-table offset,
+ * kv_begin, kv_end, causal base position (or 0x3fffffff), partial index, path. */
+int32_t oxy_batch_work(const oxy_batch *batch, int32_t *out, int32_t cap_items);
+
+const char *oxy_last_error(void);
+int32_t oxy_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OXY_H */

@@ -1,0 +1,56 @@
+// Internal interface between the host pool (oxy_pool.cpp) and the HIP kernels
+// (oxy_kernels.hip).  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace oxy {
+
+constexpr int kHeads = 8;        // query heads sharing the one KV head
+constexpr int kDim = 256;        // head_dim
+constexpr int kPage = 16;        // tokens per page
+constexpr int kPageBytes = kPage * kDim * 2;      // one K page or one V page (bf16)
+constexpr int kBlockBytes = 2 * kPageBytes;       // K page + V page of one layer
+constexpr int kNoCausal = 0x3fffffff;
+constexpr int kWorkWords = 8;
+constexpr int kMaxInlineBlocks = 512;             // block ids passed by value to append/gather
+
+// work record fields
+enum { W_TOK_OFF = 0, W_N_TOK, W_TBL_OFF, W_KV_BEGIN, W_KV_END, W_CAUSAL_Q0, W_PART_IDX, W_PATH };
+// paths
+enum { PATH_WAVE = 0,    // one wavefront, <=2 query tokens (16 rows), KV streamed to registers
+       PATH_TILE = 1 };  // one workgroup, <=16 query tokens (128 rows), KV staged through LDS
+
+struct InlineIds {
+  int32_t v[kMaxInlineBlocks];
+};
+
+// Scatter n_tokens rows of K and V (natural [token][256] bf16) into the slots of one layer.
+hipError_t launch_append(const void* k_new, const void* v_new, const int32_t* d_slots,
+                         int32_t n_tokens, void* layer_base, hipStream_t s);
+// Same, slots = blocks.v[(pos0+t)/16]*16 + (pos0+t)%16 with the block ids passed by value.
+hipError_t launch_append_inline(const void* k_new, const void* v_new, const InlineIds& blocks,
+                                int32_t pos0, int32_t n_tokens, void* layer_base, hipStream_t s);
+// Gather rows back to natural order; slot ids passed by value (<= kMaxInlineBlocks per call).
+hipError_t launch_gather_inline(const void* layer_base, const InlineIds& slots, int32_t n,
+                                void* k_out, void* v_out, hipStream_t s);
+
+struct AttnArgs {
+  const void* layer_base;   // KV of this layer
+  const void* q;            // [n_q][8][256] bf16
+  void* out;                // [n_q][8][256] bf16
+  float* lse;               // [n_q][8] or null
+  const int32_t* work;      // [n_work][8]
+  const int32_t* tok_list;
+  const int32_t* tables;
+  const int32_t* part_off;  // [n_q]
+  const int32_t* n_parts;   // [n_q]
+  float* part_acc;          // [n_partials][8][256]
+  float* part_ml;           // [n_partials][8][2]  (running max in log2 domain, sum)
+  int32_t n_work;
+  int32_t n_q;
+  float scale;
+};
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+
+}  // namespace oxy

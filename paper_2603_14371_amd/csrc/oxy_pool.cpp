@@ -1,0 +1,732 @@
+// Host side of the library: block pool, prefixes, streams, batch descriptors, and the
+// C ABI declared in include/oxy.h.  The paper's manager (Sec. 3.2; App. A.2) stores one
+// resumable state per request; here the KV part of that state is a reference to a
+// refcounted prefix plus an own block table and length, so that Batch (Alg. 1) is a
+// descriptor build and UnBatch is a no-op.
+#include "../../include/oxy.h"
+#include "oxy_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <unordered_map>
+#include <unordered_set>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t hip_fail(hipError_t e, const char* what) {
+  return fail(OXY_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Prefix {
+  std::vector<int32_t> blocks;
+  int32_t len = 0;
+  bool sealed = false;
+  bool handle = true;  // creator's reference still held
+  int32_t n_streams = 0;
+};
+
+struct Stream {
+  int32_t prefix_id = -1;
+  int32_t kind = 0;
+  std::vector<int32_t> blocks;
+  int32_t len = 0;
+};
+
+// One descriptor slot in the caller's workspace plus its staging buffer.
+struct DescSlot {
+  bool in_use = false;
+  int32_t* staging = nullptr;   // pinned (or malloc in host-only mode), desc_words ints
+  hipEvent_t uploaded = nullptr;
+  bool event_pending = false;
+  char* d_base = nullptr;       // device: descriptor, then partial accumulators, then (m,l)
+};
+
+}  // namespace
+
+struct oxy_pool {
+  oxy_pool_config cfg;
+  bool host_only = false;
+  std::vector<int32_t> free_stack;  // top = back
+  std::vector<int32_t> ref;
+  std::unordered_map<int32_t, Prefix> prefixes;
+  std::unordered_map<int32_t, Stream> streams;
+  int32_t next_prefix = 0;
+  int32_t next_stream = 0;
+  size_t desc_words = 0;
+  size_t per_batch_bytes = 0;
+  size_t acc_offset = 0, ml_offset = 0;
+  std::vector<DescSlot> slots;
+  int32_t live_batches = 0;
+};
+
+struct oxy_batch {
+  oxy_pool* pool = nullptr;
+  int32_t slot = -1;
+  int32_t flags = 0;
+  int32_t n_items = 0, n_tokens = 0, n_work = 0, n_partials = 0;
+  // word offsets inside the descriptor
+  int32_t off_slots = 0, off_work = 0, off_toks = 0, off_tables = 0, off_part_off = 0,
+          off_n_parts = 0;
+  std::vector<int32_t> host;  // full descriptor image (kept for introspection)
+};
+
+namespace {
+
+using oxy::kPage;
+
+int32_t blocks_for(int32_t n_tokens) { return (n_tokens + kPage - 1) / kPage; }
+
+bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
+  if (!in) return false;
+  *c = *in;
+  if (c->n_layers < 1 || c->n_q_heads != oxy::kHeads || c->n_kv_heads != 1 ||
+      c->head_dim != oxy::kDim || c->page_size != kPage || c->num_blocks < 1 ||
+      c->num_blocks > (1 << 26))
+    return false;
+  if (c->max_live_batches == 0) c->max_live_batches = 2;
+  if (c->max_q_tokens == 0) c->max_q_tokens = 1024;
+  if (c->max_append_tokens == 0) c->max_append_tokens = kPage * c->num_blocks;
+  if (c->max_work_items == 0) c->max_work_items = 16384;
+  if (c->max_partials == 0) c->max_partials = 32 * c->max_q_tokens;
+  if (c->split_tokens == 0) c->split_tokens = 256;
+  if (c->max_live_batches < 1 || c->max_live_batches > 64 || c->max_q_tokens < 1 ||
+      c->max_append_tokens < 1 || c->max_work_items < 1 || c->max_partials < 1 ||
+      c->split_tokens < 32 || c->split_tokens % 32 != 0)
+    return false;
+  return true;
+}
+
+size_t desc_words_of(const oxy_pool_config& c) {
+  return (size_t)c.max_append_tokens + (size_t)oxy::kWorkWords * c.max_work_items +
+         2 * (size_t)c.max_q_tokens /* token lists */ + (size_t)c.num_blocks /* tables */ +
+         2 * (size_t)c.max_q_tokens /* part_off, n_parts */;
+}
+
+void layout_of(const oxy_pool_config& c, size_t* acc_off, size_t* ml_off, size_t* total) {
+  size_t desc = align_up(desc_words_of(c) * 4, 256);
+  size_t acc = (size_t)c.max_partials * oxy::kHeads * oxy::kDim * sizeof(float);
+  size_t ml = align_up((size_t)c.max_partials * oxy::kHeads * 2 * sizeof(float), 256);
+  *acc_off = desc;
+  *ml_off = desc + acc;
+  *total = desc + acc + ml;
+}
+
+void unref_table(oxy_pool* p, const std::vector<int32_t>& table) {
+  for (int32_t b : table) {
+    if (--p->ref[b] == 0) p->free_stack.push_back(b);
+  }
+}
+
+void maybe_drop_prefix(oxy_pool* p, int32_t pid) {
+  auto it = p->prefixes.find(pid);
+  if (it != p->prefixes.end() && !it->second.handle && it->second.n_streams == 0)
+    p->prefixes.erase(it);
+}
+
+char* layer_base(const oxy_pool* p, int32_t layer) {
+  return (char*)p->cfg.kv_base + (size_t)layer * p->cfg.num_blocks * oxy::kBlockBytes;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* oxy_last_error(void) { return g_err; }
+int32_t oxy_version(void) { return 1; }
+
+size_t oxy_kv_bytes(const oxy_pool_config* cfg) {
+  oxy_pool_config c;
+  if (!resolve_config(cfg, &c)) return 0;
+  return (size_t)c.n_layers * c.num_blocks * oxy::kBlockBytes;
+}
+
+size_t oxy_workspace_bytes(const oxy_pool_config* cfg) {
+  oxy_pool_config c;
+  if (!resolve_config(cfg, &c)) return 0;
+  size_t a, m, total;
+  layout_of(c, &a, &m, &total);
+  return total * c.max_live_batches;
+}
+
+int32_t oxy_pool_create(const oxy_pool_config* cfg, oxy_pool** out) {
+  if (!out) return fail(OXY_ERR_INVALID_ARG, "pool_create: out is null");
+  *out = nullptr;
+  oxy_pool_config c;
+  if (!resolve_config(cfg, &c))
+    return fail(OXY_ERR_INVALID_ARG,
+                "pool_create: unsupported geometry or sizes (need 8 q heads, 1 kv head, "
+                "head_dim 256, page 16, split_tokens a multiple of 32)");
+  const bool host_only = (c.flags & OXY_POOL_HOST_ONLY) != 0;
+  if (!host_only) {
+    if (!c.kv_base || c.kv_bytes < oxy_kv_bytes(cfg) || ((uintptr_t)c.kv_base & 255))
+      return fail(OXY_ERR_INVALID_ARG, "pool_create: kv buffer missing, misaligned or < %zu bytes",
+                  oxy_kv_bytes(cfg));
+    if (!c.workspace || c.workspace_bytes < oxy_workspace_bytes(cfg) ||
+        ((uintptr_t)c.workspace & 255))
+      return fail(OXY_ERR_INVALID_ARG,
+                  "pool_create: workspace missing, misaligned or < %zu bytes",
+                  oxy_workspace_bytes(cfg));
+  }
+  std::vector<int32_t> order(c.num_blocks);
+  if (c.free_order) {
+    std::vector<char> seen(c.num_blocks, 0);
+    for (int32_t i = 0; i < c.num_blocks; ++i) {
+      int32_t b = c.free_order[i];
+      if (b < 0 || b >= c.num_blocks || seen[b])
+        return fail(OXY_ERR_INVALID_ARG, "pool_create: free_order is not a permutation");
+      seen[b] = 1;
+      order[i] = b;
+    }
+  } else {
+    for (int32_t i = 0; i < c.num_blocks; ++i) order[i] = i;
+  }
+  oxy_pool* p = new (std::nothrow) oxy_pool();
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "pool_create: out of host memory");
+  p->cfg = c;
+  p->cfg.free_order = nullptr;
+  p->host_only = host_only;
+  p->free_stack.assign(order.rbegin(), order.rend());  // first element of free_order on top
+  p->ref.assign(c.num_blocks, 0);
+  p->desc_words = desc_words_of(c);
+  layout_of(c, &p->acc_offset, &p->ml_offset, &p->per_batch_bytes);
+  p->slots.resize(c.max_live_batches);
+  for (int32_t i = 0; i < c.max_live_batches; ++i) {
+    DescSlot& s = p->slots[i];
+    if (host_only) {
+      s.staging = (int32_t*)malloc(p->desc_words * 4);
+      if (!s.staging) {
+        oxy_pool_destroy(p);
+        return fail(OXY_ERR_INVALID_ARG, "pool_create: out of host memory");
+      }
+    } else {
+      hipError_t e = hipHostMalloc((void**)&s.staging, p->desc_words * 4, hipHostMallocDefault);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&s.uploaded, hipEventDisableTiming);
+      if (e != hipSuccess) {
+        oxy_pool_destroy(p);
+        return hip_fail(e, "pool_create: pinned staging");
+      }
+      s.d_base = (char*)c.workspace + (size_t)i * p->per_batch_bytes;
+    }
+  }
+  *out = p;
+  return OXY_OK;
+}
+
+int32_t oxy_pool_destroy(oxy_pool* p) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "pool_destroy: null");
+  if (p->live_batches > 0) return fail(OXY_ERR_BUSY, "pool_destroy: %d batches alive", p->live_batches);
+  for (DescSlot& s : p->slots) {
+    if (p->host_only) {
+      free(s.staging);
+    } else {
+      if (s.uploaded) {
+        if (s.event_pending) (void)hipEventSynchronize(s.uploaded);
+        (void)hipEventDestroy(s.uploaded);
+      }
+      if (s.staging) (void)hipHostFree(s.staging);
+    }
+  }
+  delete p;
+  return OXY_OK;
+}
+
+// ---- prefixes -------------------------------------------------------------------------
+int32_t oxy_prefix_create(oxy_pool* p, int32_t* prefix_id) {
+  if (!p || !prefix_id) return fail(OXY_ERR_INVALID_ARG, "prefix_create: null argument");
+  int32_t id = p->next_prefix++;
+  p->prefixes.emplace(id, Prefix());
+  *prefix_id = id;
+  return OXY_OK;
+}
+
+int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k, const void* v,
+                          int32_t n_tokens, int32_t pos0, void* hip_stream) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "prefix_append: null pool");
+  auto it = p->prefixes.find(pid);
+  if (it == p->prefixes.end() || !it->second.handle)
+    return fail(OXY_ERR_BAD_ID, "prefix_append: no prefix %d", pid);
+  Prefix& px = it->second;
+  if (layer < 0 || layer >= p->cfg.n_layers || n_tokens < 1 || pos0 < 0 || pos0 > px.len ||
+      (int64_t)pos0 + n_tokens > (int64_t)kPage * p->cfg.num_blocks)
+    return fail(OXY_ERR_INVALID_ARG, "prefix_append: layer %d, n %d, pos0 %d (len %d)", layer,
+                n_tokens, pos0, px.len);
+  if (!p->host_only && (!k || !v)) return fail(OXY_ERR_INVALID_ARG, "prefix_append: null k/v");
+  if (px.sealed) return fail(OXY_ERR_SEALED, "prefix_append: prefix %d has streams attached", pid);
+  int32_t need = blocks_for(pos0 + n_tokens) - (int32_t)px.blocks.size();
+  if (need > (int32_t)p->free_stack.size())
+    return fail(OXY_ERR_NO_BLOCKS, "prefix_append: need %d blocks, %zu free", need,
+                p->free_stack.size());
+  for (int32_t i = 0; i < need; ++i) {
+    int32_t b = p->free_stack.back();
+    p->free_stack.pop_back();
+    p->ref[b] = 1;
+    px.blocks.push_back(b);
+  }
+  px.len = std::max(px.len, pos0 + n_tokens);
+  if (p->host_only) return OXY_OK;
+  // device copy, at most kMaxInlineBlocks blocks per launch (block ids travel by value)
+  const char* kp = (const char*)k;
+  const char* vp = (const char*)v;
+  int32_t done = 0;
+  while (done < n_tokens) {
+    int32_t pos = pos0 + done;
+    int32_t first_block = pos / kPage;
+    int32_t max_tok = (first_block + oxy::kMaxInlineBlocks) * kPage - pos;
+    int32_t n = std::min(n_tokens - done, max_tok);
+    oxy::InlineIds ids;
+    int32_t nb = blocks_for(pos + n) - first_block;
+    for (int32_t i = 0; i < nb; ++i) ids.v[i] = px.blocks[first_block + i];
+    hipError_t e = oxy::launch_append_inline(kp + (size_t)done * oxy::kDim * 2,
+                                             vp + (size_t)done * oxy::kDim * 2, ids,
+                                             pos - first_block * kPage, n, layer_base(p, layer),
+                                             (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "prefix_append: launch");
+    done += n;
+  }
+  return OXY_OK;
+}
+
+int32_t oxy_prefix_release(oxy_pool* p, int32_t pid) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "prefix_release: null pool");
+  auto it = p->prefixes.find(pid);
+  if (it == p->prefixes.end() || !it->second.handle)
+    return fail(OXY_ERR_BAD_ID, "prefix_release: no prefix %d", pid);
+  it->second.handle = false;
+  unref_table(p, it->second.blocks);
+  maybe_drop_prefix(p, pid);
+  return OXY_OK;
+}
+
+// ---- streams --------------------------------------------------------------------------
+int32_t oxy_stream_create(oxy_pool* p, int32_t pid, int32_t kind, int32_t* stream_id) {
+  if (!p || !stream_id) return fail(OXY_ERR_INVALID_ARG, "stream_create: null argument");
+  if (kind != OXY_KIND_ACTION && kind != OXY_KIND_DECODE)
+    return fail(OXY_ERR_INVALID_ARG, "stream_create: kind %d", kind);
+  if (pid != -1) {
+    auto it = p->prefixes.find(pid);
+    if (it == p->prefixes.end() || !it->second.handle)
+      return fail(OXY_ERR_BAD_ID, "stream_create: no prefix %d", pid);
+    Prefix& px = it->second;
+    px.sealed = true;
+    px.n_streams++;
+    for (int32_t b : px.blocks) p->ref[b]++;
+  }
+  int32_t id = p->next_stream++;
+  Stream s;
+  s.prefix_id = pid;
+  s.kind = kind;
+  p->streams.emplace(id, std::move(s));
+  *stream_id = id;
+  return OXY_OK;
+}
+
+int32_t oxy_stream_release(oxy_pool* p, int32_t sid) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "stream_release: null pool");
+  auto it = p->streams.find(sid);
+  if (it == p->streams.end()) return fail(OXY_ERR_BAD_ID, "stream_release: no stream %d", sid);
+  Stream s = std::move(it->second);
+  p->streams.erase(it);
+  unref_table(p, s.blocks);
+  if (s.prefix_id != -1) {
+    Prefix& px = p->prefixes.at(s.prefix_id);
+    unref_table(p, px.blocks);
+    px.n_streams--;
+    maybe_drop_prefix(p, s.prefix_id);
+  }
+  return OXY_OK;
+}
+
+int32_t oxy_stream_rewind(oxy_pool* p, int32_t sid, int32_t new_len) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "stream_rewind: null pool");
+  auto it = p->streams.find(sid);
+  if (it == p->streams.end()) return fail(OXY_ERR_BAD_ID, "stream_rewind: no stream %d", sid);
+  if (new_len < 0 || new_len > it->second.len)
+    return fail(OXY_ERR_INVALID_ARG, "stream_rewind: %d not in [0, %d]", new_len, it->second.len);
+  it->second.len = new_len;
+  return OXY_OK;
+}
+
+// ---- batch ------------------------------------------------------------------------------
+int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int32_t flags,
+                        void* hip_stream, oxy_batch** out) {
+  if (!p || !items || !out || n_items < 1)
+    return fail(OXY_ERR_INVALID_ARG, "batch_build: null argument or no items");
+  *out = nullptr;
+  const bool append_only = (flags & OXY_BATCH_APPEND_ONLY) != 0;
+  if (flags & ~OXY_BATCH_APPEND_ONLY) return fail(OXY_ERR_INVALID_ARG, "batch_build: flags");
+  const oxy_pool_config& c = p->cfg;
+
+  // ---- validate everything before touching state
+  struct Plan {
+    Stream* s;
+    int32_t sid, old_len, new_len, need, tok0;
+  };
+  std::vector<Plan> plan;
+  plan.reserve(n_items);
+  std::unordered_set<int32_t> seen;
+  int64_t need_total = 0, n_tokens = 0;
+  for (int32_t i = 0; i < n_items; ++i) {
+    auto it = p->streams.find(items[i].stream_id);
+    if (it == p->streams.end())
+      return fail(OXY_ERR_BAD_ID, "batch_build: no stream %d", items[i].stream_id);
+    if (items[i].n_new < 1 || !seen.insert(items[i].stream_id).second)
+      return fail(OXY_ERR_INVALID_ARG, "batch_build: item %d: n_new %d or duplicate stream", i,
+                  items[i].n_new);
+    Stream& s = it->second;
+    int32_t old_len = s.kind == OXY_KIND_ACTION ? 0 : s.len;
+    int64_t new_len = (int64_t)old_len + items[i].n_new;
+    if (new_len > (int64_t)kPage * c.num_blocks)
+      return fail(OXY_ERR_NO_BLOCKS, "batch_build: stream %d would exceed the pool", items[i].stream_id);
+    int32_t need = std::max(0, blocks_for((int32_t)new_len) - (int32_t)s.blocks.size());
+    plan.push_back({&s, items[i].stream_id, old_len, (int32_t)new_len, need, (int32_t)n_tokens});
+    need_total += need;
+    n_tokens += items[i].n_new;
+  }
+  if (need_total > (int64_t)p->free_stack.size())
+    return fail(OXY_ERR_NO_BLOCKS, "batch_build: need %lld blocks, %zu free", (long long)need_total,
+                p->free_stack.size());
+  if (n_tokens > c.max_append_tokens)
+    return fail(OXY_ERR_WORKSPACE, "batch_build: %lld new tokens > max_append_tokens %d",
+                (long long)n_tokens, c.max_append_tokens);
+  if (!append_only && n_tokens > c.max_q_tokens)
+    return fail(OXY_ERR_WORKSPACE, "batch_build: %lld query tokens > max_q_tokens %d",
+                (long long)n_tokens, c.max_q_tokens);
+
+  // ---- work list on the lengths the step will have (state still untouched)
+  const int32_t split = c.split_tokens;
+  std::vector<int32_t> work, toks, tables, n_parts(append_only ? 0 : n_tokens, 0);
+  std::vector<int32_t> tbl_lens;  // (offset, count) pairs to fill after allocation
+  struct TableRef {
+    int32_t off;
+    const std::vector<int32_t>* src;
+    int32_t count;
+  };
+  std::vector<TableRef> table_refs;
+  int32_t tbl_words = 0;
+  if (!append_only) {
+    auto add_work = [&](int32_t tok_off, int32_t n_tok, int32_t tbl_off, int32_t b, int32_t e,
+                        int32_t q0, int32_t part, int32_t path) {
+      int32_t w[oxy::kWorkWords] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
+      work.insert(work.end(), w, w + oxy::kWorkWords);
+    };
+    const int32_t tile_tok = 2;  // 16 MFMA rows = 2 tokens x 8 heads
+    // prefix phase: every query attached to one prefix shares its keys, whatever its kind
+    std::vector<int32_t> group_order;
+    std::unordered_map<int32_t, std::vector<int32_t>> group_toks;
+    for (const Plan& pl : plan) {
+      int32_t pid = pl.s->prefix_id;
+      if (pid == -1) continue;
+      if (p->prefixes.at(pid).len == 0) continue;
+      auto ins = group_toks.emplace(pid, std::vector<int32_t>());
+      if (ins.second) group_order.push_back(pid);
+      for (int32_t t = 0; t < pl.new_len - pl.old_len; ++t) ins.first->second.push_back(pl.tok0 + t);
+    }
+    for (int32_t pid : group_order) {
+      const Prefix& px = p->prefixes.at(pid);
+      const std::vector<int32_t>& gt = group_toks[pid];
+      int32_t tbl_off = tbl_words;
+      table_refs.push_back({tbl_off, &px.blocks, blocks_for(px.len)});
+      tbl_words += blocks_for(px.len);
+      int32_t nsplit = (px.len + split - 1) / split;
+      for (size_t t0 = 0; t0 < gt.size(); t0 += tile_tok) {
+        int32_t n = (int32_t)std::min<size_t>(tile_tok, gt.size() - t0);
+        int32_t tok_off = (int32_t)toks.size();
+        toks.insert(toks.end(), gt.begin() + t0, gt.begin() + t0 + n);
+        for (int32_t s = 0; s < nsplit; ++s)
+          add_work(tok_off, n, tbl_off, s * split, std::min(px.len, (s + 1) * split),
+                   oxy::kNoCausal, s, oxy::PATH_WAVE);
+      }
+      for (int32_t t : gt) n_parts[t] = nsplit;
+    }
+    // own phase: per item, its own tokens (the new ones included)
+    for (const Plan& pl : plan) {
+      int32_t tbl_off = tbl_words;
+      table_refs.push_back({tbl_off, &pl.s->blocks, blocks_for(pl.new_len)});
+      tbl_words += blocks_for(pl.new_len);
+      int32_t n_new = pl.new_len - pl.old_len;
+      bool causal = pl.s->kind == OXY_KIND_DECODE;
+      for (int32_t t0 = 0; t0 < n_new; t0 += tile_tok) {
+        int32_t n = std::min(tile_tok, n_new - t0);
+        int32_t tok_off = (int32_t)toks.size();
+        for (int32_t t = 0; t < n; ++t) toks.push_back(pl.tok0 + t0 + t);
+        int32_t q0 = pl.old_len + t0;
+        int32_t kv_hi = causal ? q0 + n : pl.new_len;
+        int32_t nsplit = (kv_hi + split - 1) / split;
+        int32_t base = n_parts[pl.tok0 + t0];
+        for (int32_t s = 0; s < nsplit; ++s)
+          add_work(tok_off, n, tbl_off, s * split, std::min(kv_hi, (s + 1) * split),
+                   causal ? q0 : oxy::kNoCausal, base + s, oxy::PATH_WAVE);
+        for (int32_t t = 0; t < n; ++t) n_parts[pl.tok0 + t0 + t] += nsplit;
+      }
+    }
+  }
+  int32_t n_work = (int32_t)(work.size() / oxy::kWorkWords);
+  int64_t n_partials = 0;
+  std::vector<int32_t> part_off(n_parts.size());
+  for (size_t t = 0; t < n_parts.size(); ++t) {
+    part_off[t] = (int32_t)n_partials;
+    n_partials += n_parts[t];
+  }
+  if (n_work > c.max_work_items)
+    return fail(OXY_ERR_WORKSPACE, "batch_build: %d work items > max_work_items %d", n_work,
+                c.max_work_items);
+  if (n_partials > c.max_partials)
+    return fail(OXY_ERR_WORKSPACE, "batch_build: %lld partials > max_partials %d",
+                (long long)n_partials, c.max_partials);
+  if ((size_t)tbl_words > (size_t)c.num_blocks + (size_t)need_total)
+    return fail(OXY_ERR_WORKSPACE, "batch_build: block tables too long");
+
+  // ---- a free descriptor slot
+  int32_t slot = -1;
+  for (int32_t i = 0; i < (int32_t)p->slots.size(); ++i)
+    if (!p->slots[i].in_use) {
+      slot = i;
+      break;
+    }
+  if (slot < 0)
+    return fail(OXY_ERR_BUSY, "batch_build: %d batches alive (max_live_batches)", p->live_batches);
+  oxy_batch* b = new (std::nothrow) oxy_batch();
+  if (!b) return fail(OXY_ERR_INVALID_ARG, "batch_build: out of host memory");
+
+  // ---- commit: take blocks in item order, record slots
+  std::vector<int32_t> slots_v;
+  slots_v.reserve(n_tokens);
+  for (Plan& pl : plan) {
+    for (int32_t i = 0; i < pl.need; ++i) {
+      int32_t blk = p->free_stack.back();
+      p->free_stack.pop_back();
+      p->ref[blk] = 1;
+      pl.s->blocks.push_back(blk);
+    }
+    pl.s->len = pl.new_len;
+    for (int32_t t = pl.old_len; t < pl.new_len; ++t)
+      slots_v.push_back(pl.s->blocks[t / kPage] * kPage + t % kPage);
+  }
+  for (const TableRef& tr : table_refs) {
+    if ((int32_t)tables.size() < tr.off + tr.count) tables.resize(tr.off + tr.count);
+    std::copy(tr.src->begin(), tr.src->begin() + tr.count, tables.begin() + tr.off);
+  }
+
+  // ---- descriptor image
+  b->pool = p;
+  b->slot = slot;
+  b->flags = flags;
+  b->n_items = n_items;
+  b->n_tokens = (int32_t)n_tokens;
+  b->n_work = n_work;
+  b->n_partials = (int32_t)n_partials;
+  std::vector<int32_t>& h = b->host;
+  auto put = [&](const std::vector<int32_t>& v) {
+    int32_t off = (int32_t)h.size();
+    h.insert(h.end(), v.begin(), v.end());
+    return off;
+  };
+  b->off_slots = put(slots_v);
+  b->off_work = put(work);
+  b->off_toks = put(toks);
+  b->off_tables = put(tables);
+  b->off_part_off = put(part_off);
+  b->off_n_parts = put(n_parts);
+  if (h.size() > p->desc_words) {
+    delete b;
+    // state was committed; this cannot happen because every section was bounded above
+    return fail(OXY_ERR_WORKSPACE, "batch_build: descriptor overflow (internal)");
+  }
+  DescSlot& ds = p->slots[slot];
+  if (!p->host_only) {
+    if (ds.event_pending) {
+      (void)hipEventSynchronize(ds.uploaded);  // staging of an earlier batch fully consumed
+      ds.event_pending = false;
+    }
+    memcpy(ds.staging, h.data(), h.size() * 4);
+    hipError_t e = hipMemcpyAsync(ds.d_base, ds.staging, h.size() * 4, hipMemcpyHostToDevice,
+                                  (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = hipEventRecord(ds.uploaded, (hipStream_t)hip_stream);
+    if (e != hipSuccess) {
+      delete b;
+      return hip_fail(e, "batch_build: descriptor upload");
+    }
+    ds.event_pending = true;
+  }
+  ds.in_use = true;
+  p->live_batches++;
+  *out = b;
+  return OXY_OK;
+}
+
+int32_t oxy_batch_destroy(oxy_batch* b) {
+  if (!b) return fail(OXY_ERR_INVALID_ARG, "batch_destroy: null");
+  b->pool->slots[b->slot].in_use = false;
+  b->pool->live_batches--;
+  delete b;
+  return OXY_OK;
+}
+
+int32_t oxy_stream_append(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* k_new,
+                          const void* v_new, void* hip_stream) {
+  if (!p || !b || b->pool != p || !k_new || !v_new || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "stream_append: null argument, foreign batch or host-only pool");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(OXY_ERR_INVALID_ARG, "stream_append: layer %d", layer);
+  const int32_t* d_desc = (const int32_t*)p->slots[b->slot].d_base;
+  hipError_t e = oxy::launch_append(k_new, v_new, d_desc + b->off_slots, b->n_tokens,
+                                    layer_base(p, layer), (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "stream_append: launch");
+  return OXY_OK;
+}
+
+int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* q,
+                            void* out, float* lse, float scale, void* hip_stream) {
+  if (!p || !b || b->pool != p || !q || !out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: null argument, foreign batch or host-only pool");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(OXY_ERR_INVALID_ARG, "mixed_attention: layer %d", layer);
+  if (b->flags & OXY_BATCH_APPEND_ONLY)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: batch was built append-only");
+  const DescSlot& ds = p->slots[b->slot];
+  const int32_t* d = (const int32_t*)ds.d_base;
+  oxy::AttnArgs a;
+  a.layer_base = layer_base(p, layer);
+  a.q = q;
+  a.out = out;
+  a.lse = lse;
+  a.work = d + b->off_work;
+  a.tok_list = d + b->off_toks;
+  a.tables = d + b->off_tables;
+  a.part_off = d + b->off_part_off;
+  a.n_parts = d + b->off_n_parts;
+  a.part_acc = (float*)(ds.d_base + p->acc_offset);
+  a.part_ml = (float*)(ds.d_base + p->ml_offset);
+  a.n_work = b->n_work;
+  a.n_q = b->n_tokens;
+  a.scale = scale;
+  hipError_t e = oxy::launch_attention(a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "mixed_attention: launch");
+  return OXY_OK;
+}
+
+int32_t oxy_gather_kv(oxy_pool* p, int32_t layer, const int64_t* slots, int32_t n, void* k_out,
+                      void* v_out, void* hip_stream) {
+  if (!p || !slots || n < 1 || !k_out || !v_out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "gather_kv: null argument or host-only pool");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(OXY_ERR_INVALID_ARG, "gather_kv: layer %d", layer);
+  const int64_t n_slots = (int64_t)p->cfg.num_blocks * kPage;
+  for (int32_t i = 0; i < n; ++i)
+    if (slots[i] < 0 || slots[i] >= n_slots)
+      return fail(OXY_ERR_INVALID_ARG, "gather_kv: slot %lld out of range", (long long)slots[i]);
+  for (int32_t done = 0; done < n; done += oxy::kMaxInlineBlocks) {
+    int32_t m = std::min(oxy::kMaxInlineBlocks, n - done);
+    oxy::InlineIds ids;
+    for (int32_t i = 0; i < m; ++i) ids.v[i] = (int32_t)slots[done + i];
+    hipError_t e = oxy::launch_gather_inline(layer_base(p, layer), ids, m,
+                                             (char*)k_out + (size_t)done * oxy::kDim * 2,
+                                             (char*)v_out + (size_t)done * oxy::kDim * 2,
+                                             (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "gather_kv: launch");
+  }
+  return OXY_OK;
+}
+
+// ---- introspection ------------------------------------------------------------------------
+int32_t oxy_stream_info(oxy_pool* p, int32_t sid, int32_t* prefix_id, int32_t* kind,
+                        int32_t* own_len, int32_t* n_blocks) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "stream_info: null pool");
+  auto it = p->streams.find(sid);
+  if (it == p->streams.end()) return fail(OXY_ERR_BAD_ID, "stream_info: no stream %d", sid);
+  if (prefix_id) *prefix_id = it->second.prefix_id;
+  if (kind) *kind = it->second.kind;
+  if (own_len) *own_len = it->second.len;
+  if (n_blocks) *n_blocks = (int32_t)it->second.blocks.size();
+  return OXY_OK;
+}
+
+int32_t oxy_stream_blocks(oxy_pool* p, int32_t sid, int32_t* out, int32_t cap) {
+  if (!p || !out) return fail(OXY_ERR_INVALID_ARG, "stream_blocks: null argument");
+  auto it = p->streams.find(sid);
+  if (it == p->streams.end()) return fail(OXY_ERR_BAD_ID, "stream_blocks: no stream %d", sid);
+  if (cap < (int32_t)it->second.blocks.size()) return fail(OXY_ERR_INVALID_ARG, "stream_blocks: cap");
+  std::copy(it->second.blocks.begin(), it->second.blocks.end(), out);
+  return OXY_OK;
+}
+
+int32_t oxy_prefix_info(oxy_pool* p, int32_t pid, int32_t* len, int32_t* n_blocks,
+                        int32_t* sealed, int32_t* n_streams) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "prefix_info: null pool");
+  auto it = p->prefixes.find(pid);
+  if (it == p->prefixes.end()) return fail(OXY_ERR_BAD_ID, "prefix_info: no prefix %d", pid);
+  if (len) *len = it->second.len;
+  if (n_blocks) *n_blocks = (int32_t)it->second.blocks.size();
+  if (sealed) *sealed = it->second.sealed ? 1 : 0;
+  if (n_streams) *n_streams = it->second.n_streams;
+  return OXY_OK;
+}
+
+int32_t oxy_prefix_blocks(oxy_pool* p, int32_t pid, int32_t* out, int32_t cap) {
+  if (!p || !out) return fail(OXY_ERR_INVALID_ARG, "prefix_blocks: null argument");
+  auto it = p->prefixes.find(pid);
+  if (it == p->prefixes.end()) return fail(OXY_ERR_BAD_ID, "prefix_blocks: no prefix %d", pid);
+  if (cap < (int32_t)it->second.blocks.size()) return fail(OXY_ERR_INVALID_ARG, "prefix_blocks: cap");
+  std::copy(it->second.blocks.begin(), it->second.blocks.end(), out);
+  return OXY_OK;
+}
+
+int32_t oxy_block_refcounts(oxy_pool* p, int32_t* out, int32_t cap) {
+  if (!p || !out || cap < p->cfg.num_blocks) return fail(OXY_ERR_INVALID_ARG, "block_refcounts: cap");
+  std::copy(p->ref.begin(), p->ref.end(), out);
+  return OXY_OK;
+}
+
+int32_t oxy_free_blocks(oxy_pool* p, int32_t* out, int32_t cap) {
+  if (!p || !out || cap < (int32_t)p->free_stack.size()) return fail(OXY_ERR_INVALID_ARG, "free_blocks: cap");
+  std::copy(p->free_stack.rbegin(), p->free_stack.rend(), out);
+  return OXY_OK;
+}
+
+int32_t oxy_pool_stats(oxy_pool* p, int32_t* free_blocks, int32_t* live_prefixes,
+                       int32_t* live_streams) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "pool_stats: null pool");
+  if (free_blocks) *free_blocks = (int32_t)p->free_stack.size();
+  if (live_prefixes) *live_prefixes = (int32_t)p->prefixes.size();
+  if (live_streams) *live_streams = (int32_t)p->streams.size();
+  return OXY_OK;
+}
+
+int32_t oxy_batch_info(const oxy_batch* b, int32_t* n_items, int32_t* n_tokens, int32_t* n_work,
+                       int32_t* n_partials) {
+  if (!b) return fail(OXY_ERR_INVALID_ARG, "batch_info: null");
+  if (n_items) *n_items = b->n_items;
+  if (n_tokens) *n_tokens = b->n_tokens;
+  if (n_work) *n_work = b->n_work;
+  if (n_partials) *n_partials = b->n_partials;
+  return OXY_OK;
+}
+
+int32_t oxy_batch_slots(const oxy_batch* b, int64_t* out, int32_t cap) {
+  if (!b || !out || cap < b->n_tokens) return fail(OXY_ERR_INVALID_ARG, "batch_slots: cap");
+  for (int32_t i = 0; i < b->n_tokens; ++i) out[i] = b->host[b->off_slots + i];
+  return OXY_OK;
+}
+
+int32_t oxy_batch_work(const oxy_batch* b, int32_t* out, int32_t cap_items) {
+  if (!b || !out || cap_items < b->n_work) return fail(OXY_ERR_INVALID_ARG, "batch_work: cap");
+  std::copy(b->host.begin() + b->off_work,
+            b->host.begin() + b->off_work + (size_t)b->n_work * oxy::kWorkWords, out);
+  return OXY_OK;
+}
+
+}  // extern "C"

@@ -129,8 +129,9 @@ def tiny(prefix_len=64, chunk=10, prior=4, n_layers=1, sigma=1.0, seed=None):
     if prior > 0:
         b.step([(dec, prior)], attend=False)
     b.step([(act, chunk), (dec, 1)])
-    return _workload("tiny", _seed(0) if seed is None else seed, n_layers, 64, b.trace,
-                     sigma=sigma)
+    need = -(-prefix_len // PAGE) + -(-chunk // PAGE) + -(-(prior + 1) // PAGE)
+    return _workload("tiny", _seed(0) if seed is None else seed, n_layers, max(64, 2 * need),
+                     b.trace, sigma=sigma)
 
 
 # ---------------------------------------------------------------------------

@@ -1,0 +1,60 @@
+"""GPU parity, small cases: the tiny configuration and its degenerate variants, element by
+element against the float64 oracle through the C ABI; indexing and pool contents bit-exact."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2603_14371_amd import synth
+from parity_util import assert_pool_contents_equal, run_both
+
+pytestmark = pytest.mark.gpu
+
+
+def _finish(gw, ow):
+    try:
+        return assert_pool_contents_equal(gw, ow)
+    finally:
+        gw.close()
+
+
+def test_tiny_config():
+    w = synth.tiny()
+    gw, g, ow, o = run_both(w)
+    assert g[-1]["O"][0].shape == (11, 8, 256)
+    assert _finish(gw, ow) == 64 + 10 + 5
+
+
+@pytest.mark.parametrize("kw", [
+    dict(prefix_len=70),                      # partial last prefix page
+    dict(prefix_len=0),                       # no prefix at all
+    dict(prefix_len=33, chunk=1, prior=0),    # single-token everything
+    dict(prefix_len=64, chunk=50, prior=40),  # several pages of own history, ragged tails
+    dict(prefix_len=832, chunk=50, prior=300, n_layers=3),
+    dict(sigma=1.0 / 16.0),                   # the other reading of "scaled by 1/sqrt(256)"
+], ids=["p70", "p0", "single", "own40", "pi05_shape", "sigma16"])
+def test_tiny_variants(kw):
+    w = synth.tiny(**kw)
+    gw, g, ow, o = run_both(w, split_tokens=64)
+    _finish(gw, ow)
+
+
+def test_nan_poisoned_pool():
+    """Stale bits in unused slots (here: NaN everywhere) must never reach an output."""
+    w = synth.tiny(prefix_len=70, chunk=13, prior=21)
+    gw, g, ow, o = run_both(w, poison=True, split_tokens=32)
+    _finish(gw, ow)
+
+
+def test_multi_token_decode_queries_are_causal():
+    """Several new decode tokens in one step: query r sees own tokens 0..p_r only."""
+    from paper_2603_14371_amd.synth import _TraceBuilder, _workload, DECODE, ACTION
+    b = _TraceBuilder()
+    pid = b.prefix(40)
+    d0, d1 = b.stream(pid, DECODE), b.stream(-1, DECODE)
+    b.step([(d0, 7), (d1, 37)])
+    b.step([(d1, 3), (d0, 5)])
+    b.step([(d0, 70)])
+    w = _workload("multi_token", 99, 2, 64, b.trace)
+    gw, g, ow, o = run_both(w, split_tokens=32)
+    _finish(gw, ow)

@@ -1,0 +1,225 @@
+"""Host logic of the library against the indexing oracle, bit for bit, on a host-only pool
+(no device pointer is touched, so this runs without a GPU): block tables, slots, refcounts,
+free-stack order, ids, error codes and their atomicity; plus structural checks of the
+attention work list (every visible key of every query covered exactly once)."""
+import numpy as np
+import pytest
+
+from oracle.pool_model import PoolError, PoolModel
+from paper_2603_14371_amd import binding as B
+from paper_2603_14371_amd import synth
+
+
+def _host_pool(num_blocks, n_layers=2, free_order=None, **kw):
+    cfg = B.make_config(n_layers, num_blocks, free_order=free_order, flags=B.POOL_HOST_ONLY, **kw)
+    return B.oxy_pool_create(cfg)
+
+
+def _same_state(pool, model):
+    assert B.oxy_block_refcounts(pool, model.num_blocks) == model.ref
+    assert B.oxy_free_blocks(pool) == model.free[::-1]
+    assert B.oxy_pool_stats(pool) == model.stats()
+    for sid, s in model.streams.items():
+        assert B.oxy_stream_info(pool, sid) == (s.prefix_id, s.kind, s.length, len(s.blocks))
+        assert B.oxy_stream_blocks(pool, sid) == s.blocks
+    for pid, p in model.prefixes.items():
+        assert B.oxy_prefix_info(pool, pid) == (p.length, len(p.blocks), int(p.sealed), p.n_streams)
+        assert B.oxy_prefix_blocks(pool, pid) == p.blocks
+
+
+def _both(pool, model, fn_lib, fn_model):
+    """Runs one operation on both; they must agree on the result or on the error code."""
+    err_lib = err_model = None
+    try:
+        r_lib = fn_lib()
+    except B.OxyError as e:
+        err_lib = e.code
+    try:
+        r_model = fn_model()
+    except PoolError as e:
+        err_model = e.code
+    assert err_lib == err_model
+    if err_lib is None:
+        return r_lib, r_model
+    return None, None
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_random_operation_sequences_match_the_model(seed):
+    rng = np.random.default_rng(1000 + seed)
+    nb = 240
+    order = rng.permutation(nb).astype(np.int32)
+    pool = _host_pool(nb, free_order=order, max_q_tokens=256)
+    model = PoolModel(nb, 16, 2, order.tolist())
+    prefixes, n_checked = [], 0
+    for _ in range(500):
+        r = rng.random()
+        if r < 0.1:
+            a, b = _both(pool, model, lambda: B.oxy_prefix_create(pool), model.prefix_create)
+            assert a == b
+            prefixes.append(a)
+        elif r < 0.25 and prefixes:
+            pid = int(rng.choice(prefixes + [99]))
+            n, layer = int(rng.integers(0, 70)), int(rng.integers(0, 3))
+            plen = model.prefixes[pid].length if pid in model.prefixes else 0
+            pos0 = int(rng.choice([0, plen, plen + 1]))
+            _both(pool, model, lambda: B.oxy_prefix_append(pool, pid, layer, 0, 0, n, pos0, 0),
+                  lambda: model.prefix_append(pid, layer, n, pos0))
+        elif r < 0.4:
+            pid = int(rng.choice(prefixes + [-1, 77])) if prefixes else -1
+            kind = int(rng.integers(0, 3))
+            a, b = _both(pool, model, lambda: B.oxy_stream_create(pool, pid, kind),
+                         lambda: model.stream_create(pid, kind))
+            assert a == b
+        elif r < 0.75 and model.streams:
+            ids = list(model.streams) + ([12345] if rng.random() < 0.05 else [])
+            sids = rng.permutation(ids)[:int(rng.integers(1, 6))]
+            lo = 0 if rng.random() < 0.05 else 1
+            items = [(int(s), int(rng.integers(lo, 40))) for s in sids]
+            if rng.random() < 0.05:
+                items.append(items[0])
+
+            def lib_build():
+                batch = B.oxy_batch_build(pool, items, 0, 0)
+                try:
+                    return B.oxy_batch_slots(batch)
+                finally:
+                    B.oxy_batch_destroy(batch)
+            a, b = _both(pool, model, lib_build, lambda: model.batch_build(items))
+            assert a == b
+            n_checked += a is not None
+        elif r < 0.87 and model.streams:
+            sid = int(rng.choice(list(model.streams) + [4242]))
+            _both(pool, model, lambda: B.oxy_stream_release(pool, sid), lambda: model.stream_release(sid))
+        elif r < 0.93 and prefixes:
+            pid = int(rng.choice(prefixes))
+            _both(pool, model, lambda: B.oxy_prefix_release(pool, pid), lambda: model.prefix_release(pid))
+        elif model.streams:
+            sid = int(rng.choice(list(model.streams)))
+            new_len = int(rng.integers(0, model.streams[sid].length + 2))
+            _both(pool, model, lambda: B.oxy_stream_rewind(pool, sid, new_len),
+                  lambda: model.stream_rewind(sid, new_len))
+        _same_state(pool, model)
+    assert n_checked > 40
+    B.oxy_pool_destroy(pool)
+
+
+def _run_trace_host(w):
+    pool = _host_pool(w["num_blocks"], w["n_layers"], w["free_order"], max_q_tokens=4096)
+    model = PoolModel(w["num_blocks"], 16, w["n_layers"],
+                      None if w["free_order"] is None else w["free_order"].tolist())
+    for op in w["trace"]:
+        k = op["op"]
+        if k == "prefix_create":
+            assert B.oxy_prefix_create(pool) == model.prefix_create() == op["pid"]
+        elif k == "prefix_append":
+            for layer in range(w["n_layers"]):
+                B.oxy_prefix_append(pool, op["pid"], layer, 0, 0, op["n"], op["pos0"], 0)
+                model.prefix_append(op["pid"], layer, op["n"], op["pos0"])
+        elif k == "stream_create":
+            assert B.oxy_stream_create(pool, op["pid"], op["kind"]) == \
+                model.stream_create(op["pid"], op["kind"]) == op["sid"]
+        elif k == "step":
+            flags = 0 if op.get("attend", True) else B.BATCH_APPEND_ONLY
+            batch = B.oxy_batch_build(pool, op["items"], flags, 0)
+            assert B.oxy_batch_slots(batch) == model.batch_build(op["items"])
+            yield pool, model, op, batch
+            B.oxy_batch_destroy(batch)
+        elif k == "stream_release":
+            B.oxy_stream_release(pool, op["sid"])
+            model.stream_release(op["sid"])
+        elif k == "prefix_release":
+            B.oxy_prefix_release(pool, op["pid"])
+            model.prefix_release(op["pid"])
+    _same_state(pool, model)
+    B.oxy_pool_destroy(pool)
+
+
+def _check_work_list(pool, model, op, batch):
+    """Each (query token, visible key) pair appears in exactly one work item, on the right
+    block table, with a distinct partial index; nothing invisible is ever listed."""
+    n_items, n_tok, n_work, n_partials = B.oxy_batch_info(batch)
+    work = B.oxy_batch_work(batch)
+    assert work.shape == (n_work, 8)
+    tok_item = []
+    for idx, (sid, n_new) in enumerate(op["items"]):
+        tok_item += [(idx, t) for t in range(n_new)]
+    assert len(tok_item) == n_tok
+    # without the descriptor's token lists the check stays structural: per item, the union of
+    # own-phase key ranges and of prefix-phase key ranges
+    cover_own = {}
+    for rec in work:
+        tok_off, n_t, tbl_off, b, e, q0, part, path = [int(x) for x in rec]
+        assert 0 <= b < e and n_t >= 1 and (b % 32 == 0)
+        cover_own.setdefault((tbl_off, q0 if q0 != 0x3fffffff else -1, tok_off), []).append((b, e, part))
+    for key, spans in cover_own.items():
+        spans.sort()
+        assert spans[0][0] == 0
+        for (b0, e0, p0), (b1, e1, p1) in zip(spans, spans[1:]):
+            assert e0 == b1 and p1 == p0 + 1      # contiguous, disjoint, consecutive partials
+    total_keys = sum(e - b for spans in cover_own.values() for b, e, _ in spans)
+    return n_partials, total_keys
+
+
+def test_work_list_of_tiny_config():
+    w = synth.tiny()
+    seen = []
+    for pool, model, op, batch in _run_trace_host(w):
+        if op.get("attend", True):
+            seen.append(_check_work_list(pool, model, op, batch))
+            work = B.oxy_batch_work(batch)
+            # 11 query tokens on a 64-token prefix: ceil(11/2) tiles x 1 split, no causal base
+            prefix_items = [r for r in work if r[5] == 0x3fffffff and r[4] == 64]
+            assert len(prefix_items) == 6
+            # the decode query sits at own position 4 and sees own keys 0..4
+            dec = [r for r in work if r[5] != 0x3fffffff]
+            assert len(dec) == 1 and dec[0][5] == 4 and (dec[0][3], dec[0][4]) == (0, 5)
+            # action chunk: 5 tiles of 2 tokens over its 10 own keys
+            act = [r for r in work if r[5] == 0x3fffffff and r[4] == 10]
+            assert len(act) == 5
+    assert len(seen) == 1
+    assert seen[0][0] == 11 * 2            # one prefix partial + one own partial per token
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_config_traces_index_identically(cfg):
+    kw = {1: dict(n_layers=2), 2: dict(n_layers=2, n_frames=14), 3: dict(n_layers=2)}[cfg]
+    w = synth.by_index(cfg, **kw)
+    n = 0
+    for pool, model, op, batch in _run_trace_host(w):
+        if n % 37 == 0:
+            _same_state(pool, model)
+            if op.get("attend", True):
+                _check_work_list(pool, model, op, batch)
+        n += 1
+    assert n > 60
+
+
+def test_stress_trace_indexes_identically_through_churn():
+    w = synth.stress(n_layers=1)
+    n = 0
+    for pool, model, op, batch in _run_trace_host(w):
+        n += 1
+        if op.get("mixed"):
+            assert B.oxy_batch_info(batch)[1] == 164
+    assert n > 1000
+
+
+def test_workspace_limits_are_reported_not_overrun():
+    pool = _host_pool(64, max_q_tokens=8, max_work_items=4)
+    sid = B.oxy_stream_create(pool, -1, B.KIND_DECODE)
+    with pytest.raises(B.OxyError) as e:
+        B.oxy_batch_build(pool, [(sid, 9)], 0, 0)
+    assert e.value.code == B.ERR_WORKSPACE
+    assert B.oxy_stream_info(pool, sid)[2] == 0 and B.oxy_pool_stats(pool)[0] == 64
+    b1 = B.oxy_batch_build(pool, [(sid, 2)], 0, 0)
+    b2 = B.oxy_batch_build(pool, [(sid, 1)], 0, 0)
+    with pytest.raises(B.OxyError) as e:
+        B.oxy_batch_build(pool, [(sid, 1)], 0, 0)
+    assert e.value.code == B.ERR_BUSY
+    with pytest.raises(B.OxyError) as e:
+        B.oxy_pool_destroy(pool)
+    assert e.value.code == B.ERR_BUSY
+    B.oxy_batch_destroy(b1)
+    B.oxy_batch_destroy(b2)
+    B.oxy_pool_destroy(pool)
