@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed action+decode attention step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: host batch build (block
+tables, slots, work list, one descriptor upload) and, for each of the 18 layers, the
+KV append of the new tokens followed by the mixed attention launch.  The default
+workload is the stress configuration (64 decode streams with own histories
+~U{1..2048} on 8 shared 2048-token prefixes, plus two 50-query action chunks, pool
+fragmented by seeded churn), because it is the one configuration whose 18 distinct
+layers (about 1.5 GB of live KV) cannot sit in the 256 MB memory-side cache, so the
+HBM roofline means something.  All inputs are synthetic, seeded, and resident in HBM
+before the timed region starts.
+
+Prints ONE JSON line.  `value` is microseconds per 18-layer mixed step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
+TOKEN_BYTES = 1024          # K + V of one token in one layer: 2 * 256 * 2 B
+QO_BYTES = 2 * 8 * 256 * 2  # one query token read + one output token written
+
+
+def _build_state(workload, device, split_tokens):
+    """Replays the set-up part of a trace (everything before its first attended step) with
+    random resident data; returns the world and the remaining steps."""
+    import torch
+    from paper_2603_14371_amd import binding as B
+    from paper_2603_14371_amd.harness import GpuWorld
+    w = workload
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False,
+                  max_partials=8192)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w["seed"])
+    L = w["n_layers"]
+    stream = torch.cuda.current_stream(device).cuda_stream
+    rest = []
+    for i, op in enumerate(w["trace"]):
+        k = op["op"]
+        if k == "step" and op.get("attend", True):
+            rest = w["trace"][i:]
+            break
+        if k == "prefix_append":
+            for layer in range(L):
+                kv = torch.randn((2, op["n"], 256), device=device, generator=gen).to(torch.bfloat16)
+                B.oxy_prefix_append(gw.pool, op["pid"], layer, kv[0].data_ptr(), kv[1].data_ptr(),
+                                    op["n"], op["pos0"], stream)
+            torch.cuda.synchronize(device)
+        elif k == "step":
+            n_tok = sum(n for _, n in op["items"])
+            batch = B.oxy_batch_build(gw.pool, op["items"], B.BATCH_APPEND_ONLY, stream)
+            if not op.get("churn"):
+                for layer in range(L):
+                    kv = torch.randn((2, n_tok, 256), device=device, generator=gen).to(torch.bfloat16)
+                    B.oxy_stream_append(gw.pool, batch, layer, kv[0].data_ptr(), kv[1].data_ptr(),
+                                        stream)
+                torch.cuda.synchronize(device)
+            B.oxy_batch_destroy(batch)
+        else:
+            gw.apply(op)
+    return gw, rest
+
+
+class StepRunner:
+    """Holds resident per-layer inputs for a fixed batch shape and runs whole steps."""
+
+    def __init__(self, gw, n_tok, device, seed):
+        import torch
+        self.gw = gw
+        self.L = gw.n_layers
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        mk = lambda *shape: torch.randn(shape, device=device, generator=gen).to(torch.bfloat16)
+        self.k = mk(self.L, n_tok, 256)
+        self.v = mk(self.L, n_tok, 256)
+        self.q = mk(self.L, n_tok, 8, 256)
+        self.o = torch.empty_like(self.q)
+        self.stream = torch.cuda.current_stream(device).cuda_stream
+        self.n_tok = n_tok
+
+    def step(self, items, events=None):
+        from paper_2603_14371_amd import binding as B
+        gw = self.gw
+        batch = B.oxy_batch_build(gw.pool, items, 0, self.stream)
+        for layer in range(self.L):
+            B.oxy_stream_append(gw.pool, batch, layer, self.k[layer].data_ptr(),
+                                self.v[layer].data_ptr(), self.stream)
+            if events is not None:
+                events[layer][0].record()
+            B.oxy_mixed_attention(gw.pool, batch, layer, self.q[layer].data_ptr(),
+                                  self.o[layer].data_ptr(), 0, gw.scale, self.stream)
+            if events is not None:
+                events[layer][1].record()
+        B.oxy_batch_destroy(batch)
+
+
+def _live_kv_tokens(gw, items):
+    """Unique KV tokens one layer of this step has to read: every distinct prefix once plus
+    every item's own tokens (after the step's append)."""
+    from paper_2603_14371_amd import binding as B
+    prefixes = {}
+    own = 0
+    for sid, n_new in items:
+        pid, kind, own_len, _ = B.oxy_stream_info(gw.pool, sid)
+        if pid != -1:
+            prefixes[pid] = B.oxy_prefix_info(gw.pool, pid)[0]
+        own += n_new if kind == B.KIND_ACTION else own_len + n_new
+    return sum(prefixes.values()) + own
+
+
+def bench_stress(args, device):
+    import torch
+    from paper_2603_14371_amd import synth
+    w = synth.stress(mixed_steps=args.warmup + args.steps + 2)
+    t0 = time.time()
+    gw, rest = _build_state(w, device, args.split_tokens)
+    setup_s = time.time() - t0
+    steps = [op for op in rest if op["op"] == "step"]
+    items = steps[0]["items"]
+    n_tok = sum(n for _, n in items)
+    runner = StepRunner(gw, n_tok, device, w["seed"] + 1)
+    for i in range(args.warmup):
+        runner.step(steps[i]["items"])
+    torch.cuda.synchronize(device)
+    kv_tokens = []
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(gw.n_layers)] for _ in range(args.steps)]
+    host_us = []
+    torch.cuda.synchronize(device)
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        kv_tokens.append(_live_kv_tokens(gw, steps[args.warmup + i]["items"]))
+        h0 = time.perf_counter()
+        runner.step(steps[args.warmup + i]["items"], events[i])
+        host_us.append((time.perf_counter() - h0) * 1e6)
+    torch.cuda.synchronize(device)
+    wall = time.perf_counter() - t_start
+    step_us = wall / args.steps * 1e6
+    attn_us = [ev[0].elapsed_time(ev[1]) * 1e3 for per_step in events for ev in per_step]
+    attn_avg_us = float(np.mean(attn_us))
+    alg_bytes = float(np.mean(kv_tokens)) * TOKEN_BYTES + n_tok * QO_BYTES
+    achieved = alg_bytes / (attn_avg_us * 1e-6) / 1e9
+    n_decode = sum(1 for sid, n in items if n == 1)
+    res = {
+        "step_us": step_us,
+        "attn_launch_us": attn_avg_us,
+        "alg_bytes_per_launch": alg_bytes,
+        "kv_gbps": achieved,
+        "decode_tokens_per_s": n_decode / (step_us * 1e-6),
+        "host_us_per_step": float(np.mean(host_us)),
+        "n_q_tokens": n_tok,
+        "setup_s": setup_s,
+        "unique_kv_tokens": float(np.mean(kv_tokens)),
+    }
+    gw.close()
+    return res
+
+
+def bench_frame(device, split_tokens, frames=3):
+    """pi0.5-shaped single frame (secondary figures): prefix append of 832 tokens x 18 layers,
+    10 mixed steps (50-query chunk + 1 decode token), then 54 decode-only steps."""
+    import torch
+    from paper_2603_14371_amd import binding as B, synth
+    w = synth.pi05_frame()
+    trace = []                      # ids continue across the repeated frames
+    for f in range(frames + 1):
+        for op in synth.pi05_frame()["trace"]:
+            op = dict(op)
+            if "pid" in op and op["pid"] >= 0:
+                op["pid"] += f
+            if "sid" in op:
+                op["sid"] += 2 * f
+            if op["op"] == "step":
+                op["items"] = [(s + 2 * f, n) for s, n in op["items"]]
+            trace.append(op)
+    w["trace"] = trace
+    from paper_2603_14371_amd.harness import GpuWorld
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False)
+    L = gw.n_layers
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1)
+    pk = torch.randn((L, 2, 832, 256), device=device, generator=gen).to(torch.bfloat16)
+    runner_mixed = StepRunner(gw, 51, device, 2)
+    runner_dec = StepRunner(gw, 1, device, 3)
+    stream = torch.cuda.current_stream(device).cuda_stream
+    t_prefix, t_mixed, t_dec = [], [], []
+    n_frame_ops = len(trace) // (frames + 1)
+    for f in range(frames + 1):
+        ops = trace[f * n_frame_ops:(f + 1) * n_frame_ops]
+        torch.cuda.synchronize(device)
+        marks = {"prefix": 0.0, "mixed": 0.0, "dec": 0.0}
+        for op in ops:
+            t0 = time.perf_counter()
+            if op["op"] == "prefix_append":
+                for layer in range(L):
+                    B.oxy_prefix_append(gw.pool, op["pid"], layer, pk[layer, 0].data_ptr(),
+                                        pk[layer, 1].data_ptr(), 832, 0, stream)
+                torch.cuda.synchronize(device)
+                marks["prefix"] += time.perf_counter() - t0
+            elif op["op"] == "step":
+                if op["mixed"]:
+                    runner_mixed.step(op["items"])
+                else:
+                    runner_dec.step(op["items"])
+                # a real decode loop needs the token of step j before step j+1: sync per step
+                torch.cuda.synchronize(device)
+                marks["mixed" if op["mixed"] else "dec"] += time.perf_counter() - t0
+            else:
+                gw.apply(op)
+        if f > 0:
+            t_prefix.append(marks["prefix"])
+            t_mixed.append(marks["mixed"])
+            t_dec.append(marks["dec"])
+    gw.close()
+    mixed_us = float(np.mean(t_mixed)) / 10 * 1e6
+    dec_us = float(np.mean(t_dec)) / 54 * 1e6
+    t_action = float(np.mean(t_prefix)) + float(np.mean(t_mixed))
+    return {
+        "prefix_append_us": float(np.mean(t_prefix)) * 1e6,
+        "mixed_step_us": mixed_us,
+        "decode_only_step_us": dec_us,
+        "action_hz": 1.0 / t_action,
+        "actions_per_s": 50.0 / t_action,
+        "decode_tokens_per_s_mixed": 1.0 / (mixed_us * 1e-6),
+        "decode_tokens_per_s_decode_only": 1.0 / (dec_us * 1e-6),
+    }
+
+
+def cpu_baseline(sample_layers=12):
+    """The float64 oracle, as it stands, on one layer of a stress-shaped mixed step."""
+    from oracle import attention
+    from paper_2603_14371_amd import synth
+    rng = np.random.default_rng(5)
+    w = synth.stress(mixed_steps=1, churn_ops=0)
+    hist = w["hist"]
+    bits = lambda *shape: synth.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+    prefixes = [(bits(2048, 256), bits(2048, 256)) for _ in range(8)]
+    own = [(bits(h + 1, 256), bits(h + 1, 256)) for h in hist]
+    qs = [bits(1, 8, 256) for _ in hist]
+    chunk = [(bits(50, 256), bits(50, 256), bits(50, 8, 256)) for _ in range(2)]
+    t0 = time.perf_counter()
+    for _ in range(sample_layers):
+        for i, (ko, vo) in enumerate(own):
+            kp, vp = prefixes[i // 8]
+            attention.attend_item(attention.DECODE, qs[i], kp, vp, ko, vo, 0.0625)
+        for i, (kc, vc, qc) in enumerate(chunk):
+            kp, vp = prefixes[i]
+            attention.attend_item(attention.ACTION, qc, kp, vp, kc, vc, 0.0625)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": dt / sample_layers * 18 * 1e6, "unit": "us/step", "cores": int(threads),
+            "kind": "oracle",
+            "sample": "%d of 18 layers of one stress mixed step (attention only), scaled x18/%d; "
+                      "host has %d cores" % (sample_layers, sample_layers, os.cpu_count())}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-frame", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sharding by prefix group is described in "
+              "DESIGN.md); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    device = torch.device("cuda:0")
+    s = bench_stress(args, device)
+    out = {
+        "metric": "mixed action+decode attention step us (18 layers: append + attention)",
+        "value": round(s["step_us"], 2), "unit": "us/step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(s["step_us"] / 1e3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "stress: 64 decode streams (own ~U{1..2048}) on 8 shared 2048-token "
+                               "prefixes + 2 action chunks of 50, 18 layers, 8q/1kv, d=256, page 16, "
+                               "fragmented pool", "q_tokens": s["n_q_tokens"],
+                   "unique_kv_tokens_per_layer": round(s["unique_kv_tokens"])},
+        "kv_hbm_gbps": round(s["kv_gbps"], 1),
+        "kv_hbm_frac_of_peak": round(s["kv_gbps"] / HBM_PEAK_GBPS, 4),
+        "decode_tokens_per_s": round(s["decode_tokens_per_s"], 1),
+        "host_us_per_step": round(s["host_us_per_step"], 1),
+        "roofline": {"bound": "hbm", "achieved": round(s["kv_gbps"], 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(s["kv_gbps"] / HBM_PEAK_GBPS, 4),
+                     "traffic": None,
+                     "kernel": "mixed attention launch (work items + merge), per layer",
+                     "launch_us": round(s["attn_launch_us"], 2),
+                     "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
+    }
+    if not args.no_frame:
+        out["pi05_frame"] = {k: round(v, 2) for k, v in bench_frame(device, args.split_tokens).items()}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

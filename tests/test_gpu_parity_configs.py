@@ -1,0 +1,120 @@
+"""GPU parity on the five workload configurations (through the C ABI, element by element
+against the float64 oracle on the same seeded bits), at their real geometry: 8 q heads over
+1 kv head, head_dim 256, page 16, 832- and 2048-token prefixes, 50-query chunks."""
+import numpy as np
+import pytest
+
+from oracle import attention
+from paper_2603_14371_amd import synth
+from parity_util import (assert_lse_close, assert_o_close, assert_pool_contents_equal, run_both)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_pi05_frame_all_64_steps_two_layers():
+    w = synth.pi05_frame()
+    gw, g, ow, o = run_both(w, layers=[0, 17])
+    gw.close()
+    steps = [r for op, r in zip(w["trace"], g) if op["op"] == "step"]
+    assert len(steps) == 64 and steps[0]["O"][17].shape == (51, 8, 256)
+    assert steps[-1]["O"][0].shape == (1, 8, 256)
+
+
+def test_config2_cross_frame_continuous_batching():
+    """Streams born in different frames keep the prefix of their birth frame and resume
+    across frames; random block placement."""
+    w = synth.cross_frame(n_frames=10, targets=[16, 37, 24, 55, 18, 70, 21, 33])
+    steps = [i for i, op in enumerate(w["trace"]) if op["op"] == "step"]
+    chosen = set(steps[::7]) | set(steps[-3:])
+    gw, g, ow, o = run_both(w, layers=[5], oracle_steps=chosen)
+    try:
+        assert_pool_contents_equal(gw, ow)
+    finally:
+        gw.close()
+    sizes = [len(w["trace"][i]["items"]) for i in steps]
+    assert max(sizes) >= 4          # an action chunk plus several carried-over requests
+
+
+def test_config3_shared_equals_isolated_bitwise_and_matches_oracle():
+    """Sec. 1 / Sec. 3.2: fanning one prefill cache out to four tasks gives what four isolated
+    runs with their own prefix copies give.  On the GPU the split of a query's keys depends
+    only on its own lengths, so the two runs agree bit for bit."""
+    kw = dict(n_steps=40)
+    shared, iso = synth.cross_task(**kw), synth.cross_task(isolated=True, **kw)
+    for w in (shared, iso):         # stop before the releases so that peak block use is visible
+        w["trace"] = [op for op in w["trace"] if "release" not in op["op"]]
+    s_steps = [i for i, op in enumerate(shared["trace"]) if op["op"] == "step"]
+    gw, gs, ow, os_ = run_both(shared, layers=[2, 9], oracle_steps=set(s_steps[::6]))
+    shared_blocks = gw.w["num_blocks"] - gw_free(gw)
+    gw.close()
+    gw, gi, _, _ = run_both(iso, layers=[2, 9], oracle_steps=set())
+    iso_blocks = gw.w["num_blocks"] - gw_free(gw)
+    gw.close()
+    by_step = {}
+    for op, r in zip(iso["trace"], gi):
+        if op["op"] == "step":
+            by_step.setdefault(op["shared_step"], []).append(r)
+    n = 0
+    for op, r in zip(shared["trace"], gs):
+        if op["op"] != "step":
+            continue
+        for layer in (2, 9):
+            cat = np.concatenate([x["O"][layer] for x in by_step[op["shared_step"]]])
+            assert np.array_equal(cat, r["O"][layer]), "step %d layer %d" % (op["shared_step"], layer)
+            n += 1
+    assert n == 80
+    assert iso_blocks - shared_blocks == 3 * 52       # three redundant copies of the prefix
+
+
+def gw_free(gw):
+    from paper_2603_14371_amd import binding as B
+    return B.oxy_pool_stats(gw.pool)[0]
+
+
+def test_config4_stress_full_size_sampled_against_oracle():
+    """Full stress geometry in the launch configuration the benchmark times (default split):
+    64 streams, histories ~U{1..2048}, 8 shared 2048-token prefixes, fragmented pool.  The
+    oracle recomputes a sample of items one by one from its un-paged lists."""
+    w = synth.stress(n_layers=18, mixed_steps=2)
+    layers = [0, 17]
+    gw, g, ow, o = run_both(w, layers=layers, oracle_steps=set(), want_lse=True)
+    try:
+        op = w["trace"][-1]
+        res = g[-1]
+        items = op["items"]
+        rng = np.random.default_rng(4)
+        starts = np.cumsum([0] + [n for _, n in items])
+        lens = [len(ow.stream_kv[sid][0][0]) for sid, _ in items]
+        pick = {0, 1, int(np.argmax(lens)), int(np.argmin(lens[2:])) + 2}
+        pick |= set(int(i) for i in rng.choice(len(items), 6, replace=False))
+        for layer in layers:
+            q_all = ow.data_fn(op["data"], layer, "q", int(starts[-1]))
+            for i in sorted(pick):
+                sid, n_new = items[i]
+                pid, kind = ow.stream_meta[sid]
+                kp, vp = ow.prefix_kv[pid][layer]
+                ko, vo = ow.stream_kv[sid][layer]
+                ref, lse = attention.attend_item(kind, q_all[starts[i]:starts[i + 1]], kp, vp, ko, vo,
+                                                 w["scale"])
+                assert_o_close(res["O"][layer][starts[i]:starts[i + 1]], ref,
+                               "item %d layer %d" % (i, layer))
+                assert_lse_close(res["LSE"][layer][starts[i]:starts[i + 1]], lse)
+        # indexing of the whole trace was compared op by op inside run_both; pool contents of a
+        # few streams bit-exact
+        for sid, _ in [items[i] for i in sorted(pick)][:4]:
+            slots = gw.stream_slots(sid)
+            gk, gv = gw.gather(17, slots)
+            assert np.array_equal(gk, ow.stream_kv[sid][17][0])
+            assert np.array_equal(gv, ow.stream_kv[sid][17][1])
+    finally:
+        gw.close()
+
+
+def test_config4_reduced_every_item_against_oracle():
+    w = synth.stress(n_layers=2, n_streams=16, group=4, prefix_len=300, hist_hi=400,
+                     num_blocks=2048, churn_ops=300, mixed_steps=2)
+    gw, g, ow, o = run_both(w, layers=[1], split_tokens=96)
+    try:
+        assert_pool_contents_equal(gw, ow)
+    finally:
+        gw.close()
