@@ -426,8 +426,12 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       int32_t w[oxy::kWorkWords] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
       work.insert(work.end(), w, w + oxy::kWorkWords);
     };
-    const int32_t tile_tok = 2;  // 16 MFMA rows = 2 tokens x 8 heads
-    // prefix phase: every query attached to one prefix shares its keys, whatever its kind
+    // Which path evaluates a query depends on its item only (kind, n_new, phase), never on its
+    // batch mates, so an item's arithmetic is the same in every batch it can appear in:
+    //   prefix phase -> tiles of up to 8 tokens sharing the prefix pages through LDS;
+    //   own phase    -> items with <= 2 new tokens (decode) stream their own pages;
+    //                   larger items (action chunks, multi-token decode) use tiles of 8.
+    const int32_t tile_tok = 8;
     std::vector<int32_t> group_order;
     std::unordered_map<int32_t, std::vector<int32_t>> group_toks;
     for (const Plan& pl : plan) {
@@ -451,19 +455,20 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         toks.insert(toks.end(), gt.begin() + t0, gt.begin() + t0 + n);
         for (int32_t s = 0; s < nsplit; ++s)
           add_work(tok_off, n, tbl_off, s * split, std::min(px.len, (s + 1) * split),
-                   oxy::kNoCausal, s, oxy::PATH_WAVE);
+                   oxy::kNoCausal, s, oxy::PATH_TILE);
       }
       for (int32_t t : gt) n_parts[t] = nsplit;
     }
-    // own phase: per item, its own tokens (the new ones included)
     for (const Plan& pl : plan) {
       int32_t tbl_off = tbl_words;
       table_refs.push_back({tbl_off, &pl.s->blocks, blocks_for(pl.new_len)});
       tbl_words += blocks_for(pl.new_len);
       int32_t n_new = pl.new_len - pl.old_len;
       bool causal = pl.s->kind == OXY_KIND_DECODE;
-      for (int32_t t0 = 0; t0 < n_new; t0 += tile_tok) {
-        int32_t n = std::min(tile_tok, n_new - t0);
+      const int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
+      const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
+      for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
+        int32_t n = std::min(step_tok, n_new - t0);
         int32_t tok_off = (int32_t)toks.size();
         for (int32_t t = 0; t < n; ++t) toks.push_back(pl.tok0 + t0 + t);
         int32_t q0 = pl.old_len + t0;
@@ -472,9 +477,27 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         int32_t base = n_parts[pl.tok0 + t0];
         for (int32_t s = 0; s < nsplit; ++s)
           add_work(tok_off, n, tbl_off, s * split, std::min(kv_hi, (s + 1) * split),
-                   causal ? q0 : oxy::kNoCausal, base + s, oxy::PATH_WAVE);
+                   causal ? q0 : oxy::kNoCausal, base + s, path);
         for (int32_t t = 0; t < n; ++t) n_parts[pl.tok0 + t0 + t] += nsplit;
       }
+    }
+    // longest work first: workgroups are handed out in index order
+    {
+      const int32_t nw = (int32_t)(work.size() / oxy::kWorkWords);
+      std::vector<int32_t> idx(nw);
+      for (int32_t i = 0; i < nw; ++i) idx[i] = i;
+      auto cost = [&](int32_t i) {
+        const int32_t* r = &work[(size_t)i * oxy::kWorkWords];
+        int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
+        return r[oxy::W_PATH] == oxy::PATH_TILE ? 2 * steps : steps;
+      };
+      std::stable_sort(idx.begin(), idx.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
+      std::vector<int32_t> sorted(work.size());
+      for (int32_t i = 0; i < nw; ++i)
+        std::copy(&work[(size_t)idx[i] * oxy::kWorkWords],
+                  &work[(size_t)idx[i] * oxy::kWorkWords] + oxy::kWorkWords,
+                  &sorted[(size_t)i * oxy::kWorkWords]);
+      work.swap(sorted);
     }
   }
   int32_t n_work = (int32_t)(work.size() / oxy::kWorkWords);
