@@ -19,7 +19,8 @@ constexpr int kMaxInlineBlocks = 512;             // block ids passed by value t
 enum { W_TOK_OFF = 0, W_N_TOK, W_TBL_OFF, W_KV_BEGIN, W_KV_END, W_CAUSAL_Q0, W_PART_IDX, W_PATH };
 // paths
 enum { PATH_STREAM = 0,  // <=2 query tokens (16 rows): 4 wavefronts split the keys, KV to registers
-       PATH_TILE = 1 };  // <=8 query tokens (64 rows): 4 wavefronts share the keys through LDS
+       PATH_TILE = 1,    // <=8 query tokens (64 rows): 4 wavefronts share the keys through LDS
+       PATH_NOOP = 2 };  // padding that keeps the index -> XCD pattern of the work list intact
 
 struct InlineIds {
   int32_t v[kMaxInlineBlocks];

@@ -226,8 +226,12 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   const char* __restrict__ base = (const char*)a.layer_base;
   const int nsteps = (wi.kv_end - wi.kv_begin + 31) >> 5;
 
-  u32x4 st[8];  // this thread's 8 x 16 B of the next stage: KA, KA, KB, KB, VA, VA, VB, VB
-  auto fetch = [&](const int s) {
+  // Each thread moves 8 x 16 B per step: K page A (2), K page B (2), V page A (2), V page B (2).
+  // Two steps are kept in flight in registers on top of the step being computed from LDS, so a
+  // workgroup has up to 64 KiB outstanding and a split costs about half as many memory
+  // latencies as it has steps.
+  u32x4 st0[8], st1[8];
+  auto fetch = [&](const int s, u32x4 (&st)[8]) {
     const int pos = wi.kv_begin + 32 * s;
     const bool has_b = pos + 16 < wi.kv_end;
     const char* pa = base + (size_t)wi.tbl[pos >> 4] * kBlockBytes;
@@ -243,43 +247,50 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       st[7] = *(const u32x4*)(pb + kPageBytes + 4096 + tid * 16);
     }
   };
-  auto commit = [&](const int stage) {
+  auto commit = [&](const int stage, const u32x4 (&st)[8]) {
     char* dst = smem + stage * kStageBytes + tid * 16;
 #pragma unroll
     for (int i = 0; i < 8; ++i) *(u32x4*)(dst + (i >> 1) * kPageBytes + (i & 1) * 4096) = st[i];
   };
-  fetch(0);
-  commit(0);
-  __syncthreads();
-  for (int s = 0; s < nsteps; ++s) {
-    if (s + 1 < nsteps) fetch(s + 1);
-    if (wave_active) {
-      const int pos = wi.kv_begin + 32 * s;
-      const bool has_b = pos + 16 < wi.kv_end;
-      const char* sk = smem + (s & 1) * kStageBytes + lane * 16;
-      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](const int s) {
+    const int pos = wi.kv_begin + 32 * s;
+    const bool has_b = pos + 16 < wi.kv_end;
+    const char* sk = smem + (s & 1) * kStageBytes + lane * 16;
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) sa = mfma16(*(const u32x4*)(sk + j * 1024), qf[j], sa);
-      if (has_b) {
+    for (int j = 0; j < 8; ++j) sa = mfma16(*(const u32x4*)(sk + j * 1024), qf[j], sa);
+    if (has_b) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          sb = mfma16(*(const u32x4*)(sk + kPageBytes + j * 1024), qf[j], sb);
-      }
-      u32x4 pf, pl;
-      softmax_step(sa, sb, has_b, pos, wi.kv_end, qpos, g, sl2, m, l, acc, pf, pl);
-      const int left = wi.kv_end - pos;
-      uint32_t mask[4];
-      value_masks(left, g, mask);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const u32x4 va = *(const u32x4*)(sk + 2 * kPageBytes + c * 1024);
-        u32x4 vb = {0, 0, 0, 0};
-        if (has_b) vb = *(const u32x4*)(sk + 3 * kPageBytes + c * 1024);
-        pv_block(acc, c, va, vb, mask, left < 32, pf, pl);
-      }
+      for (int j = 0; j < 8; ++j)
+        sb = mfma16(*(const u32x4*)(sk + kPageBytes + j * 1024), qf[j], sb);
     }
-    if (s + 1 < nsteps) commit((s + 1) & 1);
+    u32x4 pf, pl;
+    softmax_step(sa, sb, has_b, pos, wi.kv_end, qpos, g, sl2, m, l, acc, pf, pl);
+    const int left = wi.kv_end - pos;
+    uint32_t mask[4];
+    value_masks(left, g, mask);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const u32x4 va = *(const u32x4*)(sk + 2 * kPageBytes + c * 1024);
+      u32x4 vb = {0, 0, 0, 0};
+      if (has_b) vb = *(const u32x4*)(sk + 3 * kPageBytes + c * 1024);
+      pv_block(acc, c, va, vb, mask, left < 32, pf, pl);
+    }
+  };
+  // body(s, cur, nxt): cur's content (step s) already sits in LDS; nxt holds step s+1 in flight
+  auto body = [&](const int s, u32x4 (&cur)[8], const u32x4 (&nxt)[8]) {
+    if (s + 2 < nsteps) fetch(s + 2, cur);
+    if (wave_active) compute(s);
+    if (s + 1 < nsteps) commit((s + 1) & 1, nxt);
     __syncthreads();
+  };
+  fetch(0, st0);
+  if (nsteps > 1) fetch(1, st1);
+  commit(0, st0);
+  __syncthreads();
+  for (int s = 0; s < nsteps; s += 2) {
+    body(s, st0, st1);
+    if (s + 1 < nsteps) body(s + 1, st1, st0);
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
@@ -442,9 +453,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   wi.kv_end = w[W_KV_END];
   wi.q0 = w[W_CAUSAL_Q0];
   wi.part_idx = w[W_PART_IDX];
-  if (w[W_PATH] == PATH_TILE)
+  const int path = w[W_PATH];
+  if (path == PATH_TILE)
     tile_path(a, wi, smem);
-  else
+  else if (path == PATH_STREAM)
     stream_path(a, wi, smem, sml, qs);
 }
 

@@ -481,22 +481,67 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         for (int32_t t = 0; t < n; ++t) n_parts[pl.tok0 + t0 + t] += nsplit;
       }
     }
-    // longest work first: workgroups are handed out in index order
+    // Order of the work list.  Workgroup i runs on XCD i % 8 and every XCD has its own L2, so
+    // tiles that read the same pages (same table, same split) are given indices of one residue
+    // class; within a class the longest work comes first, and the classes are balanced by cost.
     {
       const int32_t nw = (int32_t)(work.size() / oxy::kWorkWords);
-      std::vector<int32_t> idx(nw);
-      for (int32_t i = 0; i < nw; ++i) idx[i] = i;
+      constexpr int kXcd = 8;
+      auto rec = [&](int32_t i) { return &work[(size_t)i * oxy::kWorkWords]; };
       auto cost = [&](int32_t i) {
-        const int32_t* r = &work[(size_t)i * oxy::kWorkWords];
+        const int32_t* r = rec(i);
         int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
         return r[oxy::W_PATH] == oxy::PATH_TILE ? 2 * steps : steps;
       };
-      std::stable_sort(idx.begin(), idx.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
-      std::vector<int32_t> sorted(work.size());
-      for (int32_t i = 0; i < nw; ++i)
-        std::copy(&work[(size_t)idx[i] * oxy::kWorkWords],
-                  &work[(size_t)idx[i] * oxy::kWorkWords] + oxy::kWorkWords,
-                  &sorted[(size_t)i * oxy::kWorkWords]);
+      std::vector<std::vector<int32_t>> groups;
+      std::unordered_map<int64_t, int32_t> group_of;
+      for (int32_t i = 0; i < nw; ++i) {
+        const int32_t* r = rec(i);
+        if (r[oxy::W_PATH] == oxy::PATH_TILE) {
+          int64_t key = ((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN];
+          auto ins = group_of.emplace(key, (int32_t)groups.size());
+          if (ins.second) groups.emplace_back();
+          groups[ins.first->second].push_back(i);
+        } else {
+          groups.push_back({i});
+        }
+      }
+      std::vector<int64_t> gcost(groups.size(), 0);
+      for (size_t gi = 0; gi < groups.size(); ++gi)
+        for (int32_t i : groups[gi]) gcost[gi] += cost(i);
+      std::vector<int32_t> gorder(groups.size());
+      for (size_t gi = 0; gi < groups.size(); ++gi) gorder[gi] = (int32_t)gi;
+      std::stable_sort(gorder.begin(), gorder.end(),
+                       [&](int32_t x, int32_t y) { return gcost[x] > gcost[y]; });
+      std::vector<int32_t> queue[kXcd];
+      int64_t qcost[kXcd] = {0};
+      for (int32_t gi : gorder) {
+        int best = 0;
+        for (int x = 1; x < kXcd; ++x)
+          if (qcost[x] < qcost[best]) best = x;
+        queue[best].insert(queue[best].end(), groups[gi].begin(), groups[gi].end());
+        qcost[best] += gcost[gi];
+      }
+      size_t longest = 0;
+      for (int x = 0; x < kXcd; ++x) {
+        std::stable_sort(queue[x].begin(), queue[x].end(),
+                         [&](int32_t a2, int32_t b2) { return cost(a2) > cost(b2); });
+        longest = std::max(longest, queue[x].size());
+      }
+      std::vector<int32_t> sorted;
+      sorted.reserve(longest * kXcd * oxy::kWorkWords);
+      const int32_t noop[oxy::kWorkWords] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
+      size_t last_real = 0;
+      for (size_t k = 0; k < longest; ++k)
+        for (int x = 0; x < kXcd; ++x) {
+          if (k < queue[x].size()) {
+            sorted.insert(sorted.end(), rec(queue[x][k]), rec(queue[x][k]) + oxy::kWorkWords);
+            last_real = sorted.size();
+          } else {
+            sorted.insert(sorted.end(), noop, noop + oxy::kWorkWords);
+          }
+        }
+      sorted.resize(last_real);
       work.swap(sorted);
     }
   }
