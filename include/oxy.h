@@ -49,12 +49,12 @@
  * Device layout of the KV buffer (private to the library, stated for the record):
  * layer l starts at l * num_blocks * 16 KiB; block b of a layer is 16 KiB: the
  * K page (8 KiB) then the V page (8 KiB).  Pages are stored in the operand
- * order of the 16x16x32 bf16 MFMA so that one wavefront-wide 16-byte-per-lane
- * load is one contiguous KiB:
- *   K page: 16-byte chunk (j, g, key), j<8, g<4, key<16, at byte ((j*4+g)*16+key)*16
- *           holds K[key][32j+8g .. 32j+8g+7].
- *   V page: 16-byte chunk (c, g, m), c<8, g<4, m<16, at byte ((c*4+g)*16+m)*16
- *           holds V[4g..4g+3][32c+m] followed by V[4g..4g+3][32c+16+m].
+ * order of the 16x16x32 bf16 MFMA, so that every MFMA operand of the attention
+ * kernel is one aligned 16-byte chunk:
+ *   K page: chunk (j, hf, g, k8), j<8, hf<2, g<4, k8<8, at byte ((((j*2+hf)*4+g)*8)+k8)*16
+ *           holds K[8hf+k8][32j+8g .. 32j+8g+7].
+ *   V page: chunk (c, gp, m), c<16, gp<2, m<16, at byte (((c*2+gp)*16)+m)*16
+ *           holds V[4gp..4gp+3][16c+m] followed by V[8+4gp..8+4gp+3][16c+m].
  * oxy_gather_kv reads tokens back in the natural [token][256] order.
  */
 #ifndef OXY_H
@@ -110,8 +110,12 @@ typedef struct {
   int32_t max_append_tokens;/* new tokens per batch, append-only ones included (0 -> 16*num_blocks) */
   int32_t max_work_items;   /* attention work items per batch (0 -> 16384)                   */
   int32_t max_partials;     /* per-token split results per batch (0 -> 32*max_q_tokens)      */
-  int32_t split_tokens;     /* KV tokens per work item, multiple of 32 (0 -> 256).  Fixed per
-                               pool so an item's arithmetic never depends on its batch mates */
+  int32_t split_tokens;     /* KV tokens per work item of the shared-tile path (prefix phase, action
+                               chunks), multiple of 32, <= 1024 (0 -> 256)                   */
+  int32_t stream_split_tokens; /* KV tokens per work item of the decode streaming path, multiple
+                               of 32, <= 1024 (0 -> split_tokens).  Both are
+                               fixed per pool so an item's arithmetic never depends on its
+                               batch mates                                                   */
   int32_t flags;
 } oxy_pool_config;
 
@@ -166,6 +170,18 @@ int32_t oxy_stream_append(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
 int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
                             const void *q, void *out, float *lse, float scale,
                             void *hip_stream);
+/* All layers [layer_begin, layer_end) of one step, in order: for each layer the append and
+ * then the mixed attention, exactly as the two calls above would enqueue them (this is their
+ * loop moved below the ABI, so a caller pays one call per step instead of two per layer).
+ * Layer l uses k_new + l*kv_layer_stride, v_new + l*kv_layer_stride (bytes), q + l*q_layer_stride,
+ * out + l*q_layer_stride, and lse + l*lse_layer_stride (bytes) when lse is not NULL.
+ * events: NULL, or HOST array of 2*(layer_end-layer_begin) hipEvent_t recorded on hip_stream
+ * immediately before and after each layer's attention launch (a profiling hook). */
+int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
+                        int32_t layer_end, const void *k_new, const void *v_new,
+                        size_t kv_layer_stride, const void *q, void *out, size_t q_layer_stride,
+                        float *lse, size_t lse_layer_stride, float scale, void *const *events,
+                        void *hip_stream);
 int32_t oxy_batch_destroy(oxy_batch *batch);
 
 /* Reads K/V rows back in natural order: slots HOST int64 [n] (block*16+offset);

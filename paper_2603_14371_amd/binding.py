@@ -23,7 +23,8 @@ EXPORTS = [
     "oxy_version", "oxy_last_error", "oxy_kv_bytes", "oxy_workspace_bytes", "oxy_pool_create",
     "oxy_pool_destroy", "oxy_prefix_create", "oxy_prefix_append", "oxy_prefix_release",
     "oxy_stream_create", "oxy_stream_release", "oxy_stream_rewind", "oxy_batch_build",
-    "oxy_stream_append", "oxy_mixed_attention", "oxy_batch_destroy", "oxy_gather_kv",
+    "oxy_stream_append", "oxy_mixed_attention", "oxy_step_layers", "oxy_batch_destroy",
+    "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
     "oxy_batch_slots", "oxy_batch_work",
@@ -46,6 +47,7 @@ class PoolConfig(ctypes.Structure):
         ("max_live_batches", ctypes.c_int32), ("max_q_tokens", ctypes.c_int32),
         ("max_append_tokens", ctypes.c_int32), ("max_work_items", ctypes.c_int32),
         ("max_partials", ctypes.c_int32), ("split_tokens", ctypes.c_int32),
+        ("stream_split_tokens", ctypes.c_int32),
         ("flags", ctypes.c_int32),
     ]
 
@@ -84,6 +86,8 @@ def lib():
             "oxy_batch_build": [vp, ctypes.POINTER(Item), i32, i32, vp, ctypes.POINTER(vp)],
             "oxy_stream_append": [vp, vp, i32, vp, vp, vp],
             "oxy_mixed_attention": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
+            "oxy_step_layers": [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp, ctypes.c_size_t,
+                                vp, ctypes.c_size_t, ctypes.c_float, ctypes.POINTER(vp), vp],
             "oxy_batch_destroy": [vp],
             "oxy_gather_kv": [vp, i32, ctypes.POINTER(ctypes.c_int64), i32, vp, vp, vp],
             "oxy_stream_info": [vp, i32, pi32, pi32, pi32, pi32],
@@ -124,12 +128,12 @@ def oxy_last_error():
 
 def make_config(n_layers, num_blocks, kv_base=0, kv_bytes=0, workspace=0, workspace_bytes=0,
                 free_order=None, max_live_batches=0, max_q_tokens=0, max_append_tokens=0,
-                max_work_items=0, max_partials=0, split_tokens=0, flags=0,
+                max_work_items=0, max_partials=0, split_tokens=0, stream_split_tokens=0, flags=0,
                 n_q_heads=8, n_kv_heads=1, head_dim=256, page_size=16):
     cfg = PoolConfig(n_layers, n_q_heads, n_kv_heads, head_dim, page_size, num_blocks,
                      kv_base or None, kv_bytes, workspace or None, workspace_bytes, None,
                      max_live_batches, max_q_tokens, max_append_tokens, max_work_items,
-                     max_partials, split_tokens, flags)
+                     max_partials, split_tokens, stream_split_tokens, flags)
     if free_order is not None:
         arr = np.ascontiguousarray(free_order, dtype=np.int32)
         cfg._keep = arr
@@ -198,6 +202,14 @@ def oxy_stream_append(pool, batch, layer, k_ptr, v_ptr, stream):
 def oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr, scale, stream):
     _check(lib().oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr or None,
                                      ctypes.c_float(scale), stream or None))
+
+
+def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride, q_ptr,
+                    out_ptr, q_layer_stride, lse_ptr, lse_layer_stride, scale, events, stream):
+    """events: None or a ctypes array of 2*(layer_end-layer_begin) raw hipEvent_t handles."""
+    _check(lib().oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride,
+                                 q_ptr, out_ptr, q_layer_stride, lse_ptr or None, lse_layer_stride,
+                                 ctypes.c_float(scale), events, stream or None))
 
 
 def oxy_batch_destroy(batch):

@@ -7,21 +7,24 @@
 // chunk for action queries.
 //
 // Evaluation scheme.  The visible set of a query is cut into (prefix | own) and each part
-// into fixed-size splits.  A work item is (<=16 query rows that share one KV source, one
-// split of that source); it yields an un-normalised partial (running max m in the log2
-// domain, sum l, accumulator acc[256]).  A second kernel merges a query's partials by the
-// log-sum-exp rule.  Because the split size is fixed per pool, the arithmetic of a query
-// never depends on what else is in the batch.
+// into fixed-size splits.  A work item is (query rows that share one KV source, one split of
+// that source); it yields an un-normalised partial (reference max m in the log2 domain, sum
+// l, accumulator acc[256]).  A second kernel merges a query's partials by the log-sum-exp
+// rule.  The split size is fixed per pool and the path that evaluates a query depends on
+// its item only, so the arithmetic of a query never depends on what else is in the batch.
 //
-// MFMA mapping (v_mfma_f32_16x16x32_bf16, lane = 16*g + n):
-//   S^T[key][row]  = sum_d K[key][d] * Q[row][d]      A = K page chunk, B = Q rows
-//       -> lane (n = row, g) receives keys 4g..4g+3 of the page
+// MFMA mapping (v_mfma_f32_16x16x32_bf16, lane = 16*g + n, keys taken 32 at a time = page A
+// and page B of the block table):
+//   S^T[key][row]  = sum_d K[key][d] * Q[row][d]      A = K chunks, B = Q rows
+//       tile hf (0,1): A-row r is key 8hf + r%8 of page r/8, so lane (n = row, g) receives
+//       the logits of keys 8hf + 4(g%2) + e, e < 4, of page g/2
 //   O^T[d][row]   += sum_key V[key][d] * P[row][key]  A = V chunk, B = P
-//       -> lane (n = row, g) accumulates d = 16c+4g..4g+3
+//       lane (g) contracts exactly the eight keys it holds logits for, all of one page, so
+//       its V operand is ONE 16-byte chunk of that page and P needs no cross-lane movement
+//       -> lane (n = row, g) accumulates d = 16c+4g..16c+4g+3
 // Both results keep "row = lane % 16", so the softmax state (m, l, rescale factor) is a
-// per-lane scalar and P feeds the second product without any cross-lane movement.  The
-// pool pages are stored in exactly the operand order these products want (see oxy.h), so
-// every wave-wide load is one contiguous KiB.
+// per-lane scalar.  The pool pages are stored in exactly the operand order these products
+// want (see oxy.h): every MFMA operand is one aligned 16-byte load.
 #include "oxy_internal.h"
 
 namespace oxy {
@@ -45,6 +48,30 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max over the four lanes {n, n+16, n+32, n+48} that hold one query row: two register swaps
+// between lane halves (v_permlane16_swap, v_permlane32_swap), no LDS round trip
+__device__ __forceinline__ float row_max4(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const uint32_t v = __float_as_uint(y);
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+// ------------------------------------------------------------------------------------------
+// page layout (see oxy.h)
+// ------------------------------------------------------------------------------------------
+// K page: chunk (j, hf, g, k8) holds K[8hf+k8][32j+8g .. +7]
+__device__ __forceinline__ int k_chunk_offset(int j, int hf, int g, int k8) {
+  return ((((j * 2 + hf) * 4 + g) * 8) + k8) * 16;
+}
+// V page: chunk (c, gp, m) holds V[4gp..4gp+3][16c+m] then V[8+4gp..8+4gp+3][16c+m]
+__device__ __forceinline__ int v_chunk_offset(int c, int gp, int m) {
+  return (((c * 2 + gp) * 16) + m) * 16;
+}
+__device__ __forceinline__ int v_slot_of_key(int key) { return ((key >> 3) << 2) | (key & 3); }
+
 // ------------------------------------------------------------------------------------------
 // append / gather
 // ------------------------------------------------------------------------------------------
@@ -54,9 +81,9 @@ __device__ __forceinline__ void append_row(const uint16_t* __restrict__ k_row,
   const int blk = slot >> 4, key = slot & 15;
   char* kp = layer_base + (size_t)blk * kBlockBytes;
   char* vp = kp + kPageBytes;
-  if (t < 32) *(u32x4*)(kp + (t * 16 + key) * 16) = *(const u32x4*)(k_row + t * 8);
-  const int d = t, c = d >> 5, hi = (d >> 4) & 1, m = d & 15, g = key >> 2, e = key & 3;
-  *(uint16_t*)(vp + ((c * 4 + g) * 16 + m) * 16 + hi * 8 + e * 2) = v_row[d];
+  if (t < 32)
+    *(u32x4*)(kp + k_chunk_offset(t >> 2, key >> 3, t & 3, key & 7)) = *(const u32x4*)(k_row + t * 8);
+  *(uint16_t*)(vp + v_chunk_offset(t >> 4, (key >> 2) & 1, t & 15) + v_slot_of_key(key) * 2) = v_row[t];
 }
 
 __global__ __launch_bounds__(256) void append_kernel(const uint16_t* __restrict__ k_new,
@@ -87,10 +114,11 @@ __global__ __launch_bounds__(256) void gather_inline_kernel(const char* __restri
   const int blk = slot >> 4, key = slot & 15;
   const char* kp = layer_base + (size_t)blk * kBlockBytes;
   const char* vp = kp + kPageBytes;
-  if (t < 32) *(u32x4*)(k_out + (size_t)tok * kDim + t * 8) = *(const u32x4*)(kp + (t * 16 + key) * 16);
-  const int d = t, c = d >> 5, hi = (d >> 4) & 1, m = d & 15, g = key >> 2, e = key & 3;
-  v_out[(size_t)tok * kDim + d] =
-      *(const uint16_t*)(vp + ((c * 4 + g) * 16 + m) * 16 + hi * 8 + e * 2);
+  if (t < 32)
+    *(u32x4*)(k_out + (size_t)tok * kDim + t * 8) =
+        *(const u32x4*)(kp + k_chunk_offset(t >> 2, key >> 3, t & 3, key & 7));
+  v_out[(size_t)tok * kDim + t] =
+      *(const uint16_t*)(vp + v_chunk_offset(t >> 4, (key >> 2) & 1, t & 15) + v_slot_of_key(key) * 2);
 }
 
 hipError_t launch_append(const void* k_new, const void* v_new, const int32_t* d_slots,
@@ -120,47 +148,72 @@ hipError_t launch_gather_inline(const void* layer_base, const InlineIds& slots, 
 // ------------------------------------------------------------------------------------------
 // attention work items
 // ------------------------------------------------------------------------------------------
-constexpr int kStageBytes = 4 * kPageBytes;          // K page A, K page B, V page A, V page B
-constexpr int kMergeStride = kDim + 4;               // floats per row in the LDS merge buffer
-constexpr int kSmemBytes = 4 * 16 * kMergeStride * 4;  // >= 2 * kStageBytes
+// LDS stage of the tile path: K page A, K page B, V page A, V page B.  K page B is skewed by
+// 128 bytes so that the 16 lanes served together (8 keys of page A, 8 of page B) hit
+// different banks.
+constexpr int kOffKA = 0;
+constexpr int kOffKB = kPageBytes + 128;
+constexpr int kOffVA = 2 * kPageBytes + 256;
+constexpr int kOffVB = kOffVA + kPageBytes;
+constexpr int kStageBytes = kOffVB + kPageBytes;      // 33024
+constexpr int kMergeStride = kDim + 4;                // floats per row in the LDS merge buffer
+constexpr int kSmemBytes = 4 * 16 * kMergeStride * 4; // 66560 >= 2 * kStageBytes
+static_assert(2 * kStageBytes <= kSmemBytes, "two stages must fit");
+constexpr float kGrow = 8.f;  // the reference max only moves when a logit exceeds it by 2^8
 
-// One 32-key step of the online softmax for the 16 rows of a wavefront.  sa/sb hold the raw
-// dot products of this lane's row with keys pos+4g+e (page A) and pos+16+4g+e (page B).
-// Updates the running max m (log2 domain), the lane-partial sum l and rescales acc; returns P
-// as hi+lo bf16 (a single bf16 rounding of P, 2^-9 relative, is too coarse for queries that see
-// only a handful of keys).
-__device__ __forceinline__ void softmax_step(const f32x4 sa, const f32x4 sb, const bool has_b,
+#ifdef OXY_DEBUG_PROBES
+__device__ unsigned long long g_dbg[16384 * 16];
+#define DBG_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) g_dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define DBG_MARK(i) do { } while (0)
+#endif
+
+// One 32-key step of the online softmax for the 16 rows of a wavefront.  s0/s1 hold the raw
+// dot products of this lane's row with keys pos + 16(g/2) + 8hf + 4(g%2) + e (hf = 0 / 1).
+// m is the reference max of the row in the scaled log2 domain.  It only moves when a logit
+// exceeds it by more than kGrow, so the 64-register rescale of acc is rare; P is then at most
+// 2^kGrow, well inside fp32/bf16 range.  P is returned as hi+lo bf16: a single bf16 rounding
+// (2^-9 relative) is too coarse for queries that see only a handful of keys.
+__device__ __forceinline__ void softmax_step(const f32x4 s0, const f32x4 s1, const bool need_mask,
                                              const int pos, const int kv_end, const int qpos,
                                              const int g, const float sl2, float& m, float& l,
                                              f32x4 (&acc)[16], u32x4& pf, u32x4& pl) {
   const float ninf = -__builtin_inff();
-  float s[8];
+  float t[8];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const int ka = pos + 4 * g + e, kb = ka + 16;
-    s[e] = (ka < kv_end && ka <= qpos) ? sa[e] * sl2 : ninf;
-    s[4 + e] = (has_b && kb < kv_end && kb <= qpos) ? sb[e] * sl2 : ninf;
+    t[e] = s0[e] * sl2;
+    t[4 + e] = s1[e] * sl2;
   }
-  float mx = s[0];
+  if (need_mask) {  // wave-uniform: only the last step of a split or the causal diagonal
+    const int k0 = pos + 16 * (g >> 1) + 4 * (g & 1);
 #pragma unroll
-  for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m, mx);
-  const float m_use = (m_new == ninf) ? 0.f : m_new;
-  const float alpha = fast_exp2(m - m_use);
+    for (int e = 0; e < 4; ++e) {
+      const int ka = k0 + e, kb = k0 + 8 + e;
+      t[e] = (ka < kv_end && ka <= qpos) ? t[e] : ninf;
+      t[4 + e] = (kb < kv_end && kb <= qpos) ? t[4 + e] : ninf;
+    }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])),
+                   fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+  mx = row_max4(mx);
+  const bool grow = mx > m + kGrow;   // also true for the first finite logit (m = -inf)
+  if (__any(grow)) {
+    const float m_new = grow ? mx : m;
+    const float alpha = grow ? fast_exp2(m - m_new) : 1.f;   // m = -inf gives 0
+    l *= alpha;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] *= alpha;
+    m = m_new;
+  }
+  const float m_use = (m == ninf) ? 0.f : m;
   float p[8], sum = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    p[e] = fast_exp2(s[e] - m_use);
+    p[e] = fast_exp2(t[e] - m_use);
     sum += p[e];
   }
-  l = l * alpha + sum;
-  m = m_new;
-  if (__any(alpha != 1.f)) {
-#pragma unroll
-    for (int c = 0; c < 16; ++c) acc[c] *= alpha;
-  }
+  l += sum;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     pf[i] = pack_bf16(p[2 * i], p[2 * i + 1]);
@@ -170,28 +223,18 @@ __device__ __forceinline__ void softmax_step(const f32x4 sa, const f32x4 sb, con
 }
 
 // Values of keys at or beyond kv_end may be stale bits (never-written slots, freed blocks):
-// they are selected to zero, not multiplied by zero.
-__device__ __forceinline__ void value_masks(const int left, const int g, uint32_t (&mask)[4]) {
+// they are selected to zero, not multiplied by zero.  `left` = valid keys in this step.
+__device__ __forceinline__ u32x4 value_mask(const int left, const int g) {
+  const int k0 = 16 * (g >> 1) + 4 * (g & 1);
+  u32x4 mask;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int k0 = 4 * g + 2 * i;
-    mask[i] = (k0 < left ? 0xffffu : 0u) | (k0 + 1 < left ? 0xffff0000u : 0u);
-    mask[2 + i] = (k0 + 16 < left ? 0xffffu : 0u) | (k0 + 17 < left ? 0xffff0000u : 0u);
+    mask[i] = (k0 + 2 * i < left ? 0xffffu : 0u) | (k0 + 2 * i + 1 < left ? 0xffff0000u : 0u);
+    mask[2 + i] = (k0 + 8 + 2 * i < left ? 0xffffu : 0u) | (k0 + 8 + 2 * i + 1 < left ? 0xffff0000u : 0u);
   }
+  return mask;
 }
 
-__device__ __forceinline__ void pv_block(f32x4 (&acc)[16], const int c, u32x4 va, u32x4 vb,
-                                         const uint32_t (&mask)[4], const bool masked,
-                                         const u32x4 pf, const u32x4 pl) {
-  if (masked) {
-    va[0] &= mask[0]; va[1] &= mask[1]; va[2] &= mask[0]; va[3] &= mask[1];
-    vb[0] &= mask[2]; vb[1] &= mask[3]; vb[2] &= mask[2]; vb[3] &= mask[3];
-  }
-  const u32x4 v0 = {va[0], va[1], vb[0], vb[1]};
-  const u32x4 v1 = {va[2], va[3], vb[2], vb[3]};
-  acc[2 * c] = mfma16(v0, pl, mfma16(v0, pf, acc[2 * c]));
-  acc[2 * c + 1] = mfma16(v1, pl, mfma16(v1, pf, acc[2 * c + 1]));
-}
 
 struct WorkItem {
   int tok_off, n_tok, kv_begin, kv_end, q0, part_idx;
@@ -227,71 +270,98 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   const int nsteps = (wi.kv_end - wi.kv_begin + 31) >> 5;
 
   // Each thread moves 8 x 16 B per step: K page A (2), K page B (2), V page A (2), V page B (2).
-  // Two steps are kept in flight in registers on top of the step being computed from LDS, so a
-  // workgroup has up to 64 KiB outstanding and a split costs about half as many memory
-  // latencies as it has steps.
+  // Two steps are kept in flight in registers on top of the step being computed from LDS.
   u32x4 st0[8], st1[8];
+  // block ids of the whole split, one per lane (a split has at most 64 pages): fetched once,
+  // then read with v_readlane, so no step waits on a scalar load before issuing its pages
+  const int pg0 = wi.kv_begin >> 4;
+  const int npg = ((wi.kv_end + 15) >> 4) - pg0;
+  const int ids = wi.tbl[pg0 + (lane < npg ? lane : 0)];
+  // Every fetch issues exactly eight loads and no fetch is conditional: the compiler counts
+  // outstanding loads per control-flow path, and a conditional load would make it wait for
+  // everything at the next join.  A step past the end re-reads one hot 4 KiB (eight times the
+  // same 16 B per thread); a missing page B re-reads page A.  Neither is ever used.
   auto fetch = [&](const int s, u32x4 (&st)[8]) {
-    const int pos = wi.kv_begin + 32 * s;
-    const bool has_b = pos + 16 < wi.kv_end;
-    const char* pa = base + (size_t)wi.tbl[pos >> 4] * kBlockBytes;
-    st[0] = *(const u32x4*)(pa + tid * 16);
-    st[1] = *(const u32x4*)(pa + 4096 + tid * 16);
-    st[4] = *(const u32x4*)(pa + kPageBytes + tid * 16);
-    st[5] = *(const u32x4*)(pa + kPageBytes + 4096 + tid * 16);
-    if (has_b) {
-      const char* pb = base + (size_t)wi.tbl[(pos >> 4) + 1] * kBlockBytes;
-      st[2] = *(const u32x4*)(pb + tid * 16);
-      st[3] = *(const u32x4*)(pb + 4096 + tid * 16);
-      st[6] = *(const u32x4*)(pb + kPageBytes + tid * 16);
-      st[7] = *(const u32x4*)(pb + kPageBytes + 4096 + tid * 16);
-    }
+    const bool real = s < nsteps;
+    const int pi = real ? 2 * s : 0;                      // page index inside the split
+    const int o = real ? 1 : 0;
+    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
+    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const char* pa = base + (size_t)blk_a * kBlockBytes + tid * 16;
+    const char* pb = base + (size_t)blk_b * kBlockBytes + tid * 16;
+    st[0] = *(const u32x4*)(pa);
+    st[1] = *(const u32x4*)(pa + o * 4096);
+    st[2] = *(const u32x4*)(pb);
+    st[3] = *(const u32x4*)(pb + o * 4096);
+    st[4] = *(const u32x4*)(pa + o * kPageBytes);
+    st[5] = *(const u32x4*)(pa + o * (kPageBytes + 4096));
+    st[6] = *(const u32x4*)(pb + o * kPageBytes);
+    st[7] = *(const u32x4*)(pb + o * (kPageBytes + 4096));
   };
   auto commit = [&](const int stage, const u32x4 (&st)[8]) {
     char* dst = smem + stage * kStageBytes + tid * 16;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) *(u32x4*)(dst + (i >> 1) * kPageBytes + (i & 1) * 4096) = st[i];
+    *(u32x4*)(dst + kOffKA) = st[0];
+    *(u32x4*)(dst + kOffKA + 4096) = st[1];
+    *(u32x4*)(dst + kOffKB) = st[2];
+    *(u32x4*)(dst + kOffKB + 4096) = st[3];
+    *(u32x4*)(dst + kOffVA) = st[4];
+    *(u32x4*)(dst + kOffVA + 4096) = st[5];
+    *(u32x4*)(dst + kOffVB) = st[6];
+    *(u32x4*)(dst + kOffVB + 4096) = st[7];
   };
+  // per-lane LDS offsets of this lane's operands: K of key n%8 in page n/8, V of page g/2
+  const int lds_k = ((n >> 3) ? kOffKB : kOffKA) + (g * 8 + (n & 7)) * 16;
+  const int lds_v = ((g >> 1) ? kOffVB : kOffVA) + ((g & 1) * 16 + n) * 16;
   auto compute = [&](const int s) {
     const int pos = wi.kv_begin + 32 * s;
-    const bool has_b = pos + 16 < wi.kv_end;
-    const char* sk = smem + (s & 1) * kStageBytes + lane * 16;
-    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    const int left = wi.kv_end - pos;
+    const char* sk = smem + (s & 1) * kStageBytes;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sa = mfma16(*(const u32x4*)(sk + j * 1024), qf[j], sa);
-    if (has_b) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        sb = mfma16(*(const u32x4*)(sk + kPageBytes + j * 1024), qf[j], sb);
+    for (int j = 0; j < 8; ++j) {
+      s0 = mfma16(*(const u32x4*)(sk + lds_k + j * 1024), qf[j], s0);
+      s1 = mfma16(*(const u32x4*)(sk + lds_k + j * 1024 + 512), qf[j], s1);
     }
     u32x4 pf, pl;
-    softmax_step(sa, sb, has_b, pos, wi.kv_end, qpos, g, sl2, m, l, acc, pf, pl);
-    const int left = wi.kv_end - pos;
-    uint32_t mask[4];
-    value_masks(left, g, mask);
+    softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
+                 pf, pl);
+    const bool masked = left < 32;   // wave-uniform
+    const u32x4 mask = value_mask(left, g);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const u32x4 va = *(const u32x4*)(sk + 2 * kPageBytes + c * 1024);
-      u32x4 vb = {0, 0, 0, 0};
-      if (has_b) vb = *(const u32x4*)(sk + 3 * kPageBytes + c * 1024);
-      pv_block(acc, c, va, vb, mask, left < 32, pf, pl);
+    for (int c = 0; c < 16; ++c) {
+      u32x4 v = *(const u32x4*)(sk + lds_v + c * 512);
+      if (masked) v &= mask;
+      acc[c] = mfma16(v, pl, mfma16(v, pf, acc[c]));
     }
   };
-  // body(s, cur, nxt): cur's content (step s) already sits in LDS; nxt holds step s+1 in flight
+  // body(s, cur, nxt): cur's content (step s) already sits in LDS, nxt holds step s+1 in
+  // flight.  The scheduling barriers keep the order "issue s+2, compute s, then wait for s+1",
+  // otherwise the wait would be hoisted above the compute.
   auto body = [&](const int s, u32x4 (&cur)[8], const u32x4 (&nxt)[8]) {
-    if (s + 2 < nsteps) fetch(s + 2, cur);
-    if (wave_active) compute(s);
-    if (s + 1 < nsteps) commit((s + 1) & 1, nxt);
+    if (s == 3) DBG_MARK(8);
+    fetch(s + 2, cur);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s == 3) DBG_MARK(9);
+    if (wave_active && s < nsteps) compute(s);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s == 3) DBG_MARK(10);
+    commit((s + 1) & 1, nxt);
+    if (s == 3) DBG_MARK(11);
     __syncthreads();
+    if (s == 3) DBG_MARK(12);
   };
+  DBG_MARK(1);
   fetch(0, st0);
-  if (nsteps > 1) fetch(1, st1);
+  fetch(1, st1);
+  __builtin_amdgcn_sched_barrier(0);
   commit(0, st0);
   __syncthreads();
-  for (int s = 0; s < nsteps; s += 2) {
+  DBG_MARK(2);
+  for (int s = 0; s < nsteps; s += 2) {   // steps in pairs; a step past the end moves dummies
     body(s, st0, st1);
-    if (s + 1 < nsteps) body(s + 1, st1, st0);
+    body(s + 1, st1, st0);
   }
+  DBG_MARK(3);
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   if (row_valid) {
@@ -318,8 +388,49 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const bool row_valid = ts < wi.n_tok;
   const int tok = row_valid ? a.tok_list[wi.tok_off + ts] : 0;
   const int qpos = wi.q0 + ts;
-  // the 16 query rows are the same for all four wavefronts: keep their MFMA fragments in LDS
-  // (registers are needed for the pages in flight)
+  float m = -__builtin_inff(), l = 0.f;
+  f32x4 acc[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const float sl2 = a.scale * 1.4426950408889634f;
+  const char* __restrict__ base = (const char*)a.layer_base;
+  const int nsteps = (wi.kv_end - wi.kv_begin + 31) >> 5;
+
+  u32x4 kr[16], vr[16];   // kr[2j+hf]: K chunk of (j, hf); vr[c]: V chunk of block c
+  const int pg0 = wi.kv_begin >> 4;
+  const int npg = ((wi.kv_end + 15) >> 4) - pg0;
+  const int ids = wi.tbl[pg0 + (lane < npg ? lane : 0)];   // block ids of the split, one per lane
+  const int lane_k = (g * 8 + (n & 7)) * 16;
+  const int lane_v = kPageBytes + ((g & 1) * 16 + n) * 16;
+  // Always sixteen loads per call and no conditional call (see tile_path): a step past the end
+  // re-reads the same 16 B sixteen times, a missing page B re-reads page A; neither is used.
+  auto load_k = [&](const int s) {
+    const bool real = s < nsteps;
+    const int pi = real ? 2 * s : 0;
+    const int o = real ? 512 : 0;
+    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
+    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const char* p = base + (size_t)((n >> 3) ? blk_b : blk_a) * kBlockBytes + lane_k;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) kr[i] = *(const u32x4*)(p + i * o);
+  };
+  auto load_v = [&](const int s) {
+    const bool real = s < nsteps;
+    const int pi = real ? 2 * s : 0;
+    const int o = real ? 512 : 0;
+    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
+    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const char* p = base + (size_t)((g >> 1) ? blk_b : blk_a) * kBlockBytes + lane_v;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * o);
+  };
+  DBG_MARK(1);
+  int s = wv;
+  load_k(s);
+  load_v(s);
+  // The 16 query rows are the same for all four wavefronts: their MFMA fragments live in LDS
+  // (registers are needed for the pages in flight).  Staged after the first pages are on
+  // their way, so the barrier costs no memory latency of its own.
   {
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
     const u32x4 z = {0, 0, 0, 0};
@@ -331,72 +442,36 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   }
   __syncthreads();
   const char* qf = qs + lane * 16;
-  float m = -__builtin_inff(), l = 0.f;
-  f32x4 acc[16];
-#pragma unroll
-  for (int c = 0; c < 16; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  const float sl2 = a.scale * 1.4426950408889634f;
-  const char* __restrict__ base = (const char*)a.layer_base + lane * 16;
-  const int nsteps = (wi.kv_end - wi.kv_begin + 31) >> 5;
-
-  u32x4 kr[16], vr[16];
-  auto load_k = [&](const int s) {
-    const int pos = wi.kv_begin + 32 * s;
-    const char* pa = base + (size_t)wi.tbl[pos >> 4] * kBlockBytes;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) kr[j] = *(const u32x4*)(pa + j * 1024);
-    if (pos + 16 < wi.kv_end) {
-      const char* pb = base + (size_t)wi.tbl[(pos >> 4) + 1] * kBlockBytes;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) kr[8 + j] = *(const u32x4*)(pb + j * 1024);
-    }
-  };
-  auto load_v = [&](const int s) {
-    const int pos = wi.kv_begin + 32 * s;
-    const char* pa = base + (size_t)wi.tbl[pos >> 4] * kBlockBytes + kPageBytes;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) vr[c] = *(const u32x4*)(pa + c * 1024);
-    if (pos + 16 < wi.kv_end) {
-      const char* pb = base + (size_t)wi.tbl[(pos >> 4) + 1] * kBlockBytes + kPageBytes;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) vr[8 + c] = *(const u32x4*)(pb + c * 1024);
-    }
-  };
-  int s = wv;
-  if (s < nsteps) {
-    load_k(s);
-    load_v(s);
-  }
   for (; s < nsteps; s += 4) {
     const int pos = wi.kv_begin + 32 * s;
-    const bool has_b = pos + 16 < wi.kv_end;
-    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    const int left = wi.kv_end - pos;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sa = mfma16(kr[j], *(const u32x4*)(qf + j * 1024), sa);
-    if (has_b) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) sb = mfma16(kr[8 + j], *(const u32x4*)(qf + j * 1024), sb);
+    for (int j = 0; j < 8; ++j) {
+      const u32x4 q = *(const u32x4*)(qf + j * 1024);
+      s0 = mfma16(kr[2 * j], q, s0);
+      s1 = mfma16(kr[2 * j + 1], q, s1);
     }
     u32x4 pf, pl;
-    softmax_step(sa, sb, has_b, pos, wi.kv_end, qpos, g, sl2, m, l, acc, pf, pl);
+    softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
+                 pf, pl);
     __builtin_amdgcn_sched_barrier(0);  // the next K pages reuse kr[]: issue only after S
-    if (s + 4 < nsteps) load_k(s + 4);
+    load_k(s + 4);
     __builtin_amdgcn_sched_barrier(0);
-    const int left = wi.kv_end - pos;
-    uint32_t mask[4];
-    value_masks(left, g, mask);
+    if (left < 32) {   // wave-uniform; only the last step of a split
+      const u32x4 mask = value_mask(left, g);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      u32x4 vb = {0, 0, 0, 0};
-      if (has_b) vb = vr[8 + c];
-      pv_block(acc, c, vr[c], vb, mask, left < 32, pf, pl);
+      for (int c = 0; c < 16; ++c) vr[c] &= mask;
     }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] = mfma16(vr[c], pl, mfma16(vr[c], pf, acc[c]));
     __builtin_amdgcn_sched_barrier(0);  // likewise vr[]
-    if (s + 4 < nsteps) load_v(s + 4);
+    load_v(s + 4);
     __builtin_amdgcn_sched_barrier(0);
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
+  DBG_MARK(3);
   // combine the four wavefronts' results (log-sum-exp rule) and write one partial
   float* sm = (float*)smem;
 #pragma unroll
@@ -454,42 +529,96 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   wi.q0 = w[W_CAUSAL_Q0];
   wi.part_idx = w[W_PART_IDX];
   const int path = w[W_PATH];
-  if (path == PATH_TILE)
+  DBG_MARK(0);
+  if (path == PATH_TILE) {
+    __builtin_amdgcn_s_setprio(2);   // compute-heavy: issue ahead of co-resident streaming waves
     tile_path(a, wi, smem);
-  else if (path == PATH_STREAM)
+  } else if (path == PATH_STREAM) {
     stream_path(a, wi, smem, sml, qs);
+  } else {
+    return;   // padding record
+  }
+  DBG_MARK(4);
+#ifdef OXY_DEBUG_PROBES
+  if (threadIdx.x == 0 && blockIdx.x < 16384) {
+    g_dbg[blockIdx.x * 16 + 5] = path;
+    g_dbg[blockIdx.x * 16 + 6] = (wi.kv_end - wi.kv_begin + 31) >> 5;
+    g_dbg[blockIdx.x * 16 + 7] = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);  // XCC_ID
+  }
+#endif
 }
 
+#ifdef OXY_DEBUG_PROBES
+extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), (size_t)n_words * 8);
+}
+#endif
+
 // ------------------------------------------------------------------------------------------
-// merge of a query token's partials (log-sum-exp rule), one workgroup per token
+// merge of a query token's partials (log-sum-exp rule).  Two workgroups per token (four heads
+// each); a thread owns four consecutive output dims of one head and walks the token's
+// partials with independent 16-byte loads.
 // ------------------------------------------------------------------------------------------
+constexpr int kMergeChunk = 32;   // partials whose (m, l) are staged at once
+
 __global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) {
-  const int tok = blockIdx.x, t = threadIdx.x;
-  const int h = t >> 5, d0 = (t & 31) * 8;
+  __shared__ float s_ml[kMergeChunk][4][2];
+  const int tok = blockIdx.x >> 1, t = threadIdx.x;
+  const int hw = t >> 6;                         // head within this workgroup's four
+  const int h = ((blockIdx.x & 1) << 2) | hw, d0 = (t & 63) * 4;
   const int np = a.n_parts[tok];
   const size_t base = (size_t)a.part_off[tok];
+  const float* ml = a.part_ml + (base * kHeads + ((blockIdx.x & 1) << 2)) * 2;
+  const float* src = a.part_acc + (base * kHeads + h) * kDim + d0;
+  // reference max over all partials first (the (m, l) pairs are tiny: one load per thread)
   float big = -__builtin_inff();
-  for (int p = 0; p < np; ++p) big = fmaxf(big, a.part_ml[((base + p) * kHeads + h) * 2]);
+  for (int p0 = 0; p0 < np; p0 += 32) {
+    const int p = p0 + (t >> 3), e = t & 7;      // 32 partials x 4 heads x (m, l) per pass
+    float v = -__builtin_inff();
+    if (p < np && !(e & 1)) v = ml[(size_t)p * kHeads * 2 + e];
+    // heads are e >> 1; keep only this thread's head when reducing
+    s_ml[t >> 3][e >> 1][e & 1] = v;
+    __syncthreads();
+    for (int q = 0; q < 32 && p0 + q < np; ++q) big = fmaxf(big, s_ml[q][hw][0]);
+    __syncthreads();
+  }
   float total = 0.f;
-  float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int p = 0; p < np; ++p) {
-    const float mp = a.part_ml[((base + p) * kHeads + h) * 2];
-    const float lp = a.part_ml[((base + p) * kHeads + h) * 2 + 1];
-    const float wgt = fast_exp2(mp - big);
-    total += wgt * lp;
-    const float* src = a.part_acc + ((base + p) * kHeads + h) * kDim + d0;
-    const f32x4 x = *(const f32x4*)src, y = *(const f32x4*)(src + 4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      o[e] += wgt * x[e];
-      o[4 + e] += wgt * y[e];
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
+    const int cnt = min(kMergeChunk, np - p0);
+    {
+      const int p = p0 + (t >> 3), e = t & 7;
+      s_ml[t >> 3][e >> 1][e & 1] = (p < np) ? ml[(size_t)p * kHeads * 2 + e] : 0.f;
     }
+    __syncthreads();
+    const float* sp = src + (size_t)p0 * kHeads * kDim;
+    int q = 0;
+    for (; q + 8 <= cnt; q += 8) {               // eight independent 16-byte loads in flight
+      f32x4 x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = *(const f32x4*)(sp + (size_t)(q + u) * kHeads * kDim);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float wgt = fast_exp2(s_ml[q + u][hw][0] - big);
+        total = __builtin_fmaf(wgt, s_ml[q + u][hw][1], total);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, x[u][e], o[e]);
+      }
+    }
+    for (; q < cnt; ++q) {
+      const f32x4 x = *(const f32x4*)(sp + (size_t)q * kHeads * kDim);
+      const float wgt = fast_exp2(s_ml[q][hw][0] - big);
+      total = __builtin_fmaf(wgt, s_ml[q][hw][1], total);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, x[e], o[e]);
+    }
+    __syncthreads();
   }
   const float inv = 1.f / total;
-  const u32x4 packed = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
-                        pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
-  *(u32x4*)((uint16_t*)a.out + ((size_t)tok * kHeads + h) * kDim + d0) = packed;
-  if (a.lse && (t & 31) == 0)
+  typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+  const u32x2 packed = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
+  *(u32x2*)((uint16_t*)a.out + ((size_t)tok * kHeads + h) * kDim + d0) = packed;
+  if (a.lse && (t & 63) == 0)
     a.lse[(size_t)tok * kHeads + h] = (big + __builtin_amdgcn_logf(total)) * 0.6931471805599453f;
 }
 
@@ -498,7 +627,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   attn_kernel<<<a.n_work, 256, 0, s>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  merge_kernel<<<a.n_q, 256, 0, s>>>(a);
+  merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -106,9 +106,12 @@ bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
   if (c->max_work_items == 0) c->max_work_items = 16384;
   if (c->max_partials == 0) c->max_partials = 32 * c->max_q_tokens;
   if (c->split_tokens == 0) c->split_tokens = 256;
+  if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens;
   if (c->max_live_batches < 1 || c->max_live_batches > 64 || c->max_q_tokens < 1 ||
       c->max_append_tokens < 1 || c->max_work_items < 1 || c->max_partials < 1 ||
-      c->split_tokens < 32 || c->split_tokens % 32 != 0)
+      c->split_tokens < 32 || c->split_tokens % 32 != 0 || c->split_tokens > 1024 ||
+      c->stream_split_tokens < 32 || c->stream_split_tokens % 32 != 0 ||
+      c->stream_split_tokens > 1024)
     return false;
   return true;
 }
@@ -467,6 +470,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       bool causal = pl.s->kind == OXY_KIND_DECODE;
       const int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
+      const int32_t split = n_new <= 2 ? c.stream_split_tokens : c.split_tokens;
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
         int32_t n = std::min(step_tok, n_new - t0);
         int32_t tok_off = (int32_t)toks.size();
@@ -481,6 +485,15 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         for (int32_t t = 0; t < n; ++t) n_parts[pl.tok0 + t0 + t] += nsplit;
       }
     }
+#ifdef OXY_DEBUG_PROBES
+    if (const char* dbg = getenv("OXY_DEBUG_ONLY_PATH")) {  // timing probe, never built by default
+      int keep = atoi(dbg);
+      std::vector<int32_t> kept;
+      for (size_t i = 0; i < work.size(); i += oxy::kWorkWords)
+        if (work[i + oxy::W_PATH] == keep) kept.insert(kept.end(), &work[i], &work[i] + oxy::kWorkWords);
+      work.swap(kept);
+    }
+#endif
     // Order of the work list.  Workgroup i runs on XCD i % 8 and every XCD has its own L2, so
     // tiles that read the same pages (same table, same split) are given indices of one residue
     // class; within a class the longest work comes first, and the classes are balanced by cost.
@@ -685,6 +698,35 @@ int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, cons
   a.scale = scale;
   hipError_t e = oxy::launch_attention(a, (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e, "mixed_attention: launch");
+  return OXY_OK;
+}
+
+int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, int32_t layer_end,
+                        const void* k_new, const void* v_new, size_t kv_layer_stride,
+                        const void* q, void* out, size_t q_layer_stride, float* lse,
+                        size_t lse_layer_stride, float scale, void* const* events,
+                        void* hip_stream) {
+  if (!p || layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: layers [%d, %d)", layer_begin, layer_end);
+  for (int32_t layer = layer_begin; layer < layer_end; ++layer) {
+    const size_t i = (size_t)(layer - layer_begin);
+    int32_t rc = oxy_stream_append(p, b, layer, (const char*)k_new + (size_t)layer * kv_layer_stride,
+                                   (const char*)v_new + (size_t)layer * kv_layer_stride, hip_stream);
+    if (rc != OXY_OK) return rc;
+    if (events) {
+      hipError_t e = hipEventRecord((hipEvent_t)events[2 * i], (hipStream_t)hip_stream);
+      if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    }
+    rc = oxy_mixed_attention(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
+                             (char*)out + (size_t)layer * q_layer_stride,
+                             lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
+                             scale, hip_stream);
+    if (rc != OXY_OK) return rc;
+    if (events) {
+      hipError_t e = hipEventRecord((hipEvent_t)events[2 * i + 1], (hipStream_t)hip_stream);
+      if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    }
+  }
   return OXY_OK;
 }
 

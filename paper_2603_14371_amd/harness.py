@@ -34,6 +34,7 @@ class GpuWorld:
     """Owns the device buffers of one pool and applies trace operations to it."""
 
     def __init__(self, workload, data_fn=None, layers=None, device="cuda:0", split_tokens=0,
+                 stream_split_tokens=0,
                  max_live_batches=2, max_q_tokens=None, max_append_tokens=None,
                  max_work_items=0, max_partials=0, want_lse=True, poison=False):
         if not torch.cuda.is_available():
@@ -51,7 +52,8 @@ class GpuWorld:
                             max_live_batches=max_live_batches,
                             max_q_tokens=max_q_tokens or mq, max_append_tokens=max_append_tokens or ma,
                             max_work_items=max_work_items, max_partials=max_partials,
-                            split_tokens=split_tokens)
+                            split_tokens=split_tokens,
+                            stream_split_tokens=stream_split_tokens)
         kv_bytes = B.oxy_kv_bytes(cfg)
         ws_bytes = B.oxy_workspace_bytes(cfg)
         if kv_bytes == 0 or ws_bytes == 0:
