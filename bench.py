@@ -254,6 +254,66 @@ def bench_frame(device, split_tokens, frames=3):
     }
 
 
+def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
+    """Cross-task sharing vs isolated execution on identical shapes: one refcounted 832-token
+    prefix with one batch per step, against four prefix copies with one batch per task per step
+    (the paper's "isolated execution" baseline).  Whole trace: prefix appends + n_steps steps."""
+    import torch
+    from paper_2603_14371_amd import binding as B, synth
+    from paper_2603_14371_amd.harness import GpuWorld
+    out = {}
+    for name, isolated in (("shared", False), ("isolated", True)):
+        times, blocks = [], 0
+        for rep in range(reps + 1):
+            w = synth.cross_task(isolated=isolated, n_steps=n_steps)
+            gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False,
+                          max_q_tokens=64, max_append_tokens=1024)
+            L = gw.n_layers
+            gen = torch.Generator(device=device)
+            gen.manual_seed(7)
+            pk = torch.randn((L, 2, 832, 256), device=device, generator=gen).to(torch.bfloat16)
+            runner = StepRunner(gw, 53, device, 8)
+            stream = runner.stream
+            torch.cuda.synchronize(device)
+            t0 = time.perf_counter()
+            for op in w["trace"]:
+                if op["op"] == "prefix_append":
+                    for layer in range(L):
+                        B.oxy_prefix_append(gw.pool, op["pid"], layer, pk[layer, 0].data_ptr(),
+                                            pk[layer, 1].data_ptr(), op["n"], op["pos0"], stream)
+                elif op["op"] == "step":
+                    runner.step(op["items"])
+                elif "release" in op["op"]:
+                    if blocks == 0:
+                        blocks = w["num_blocks"] - B.oxy_pool_stats(gw.pool)[0]
+                    gw.apply(op)
+                else:
+                    gw.apply(op)
+            torch.cuda.synchronize(device)
+            if rep > 0:
+                times.append(time.perf_counter() - t0)
+            gw.close()
+        out[name + "_us"] = float(np.median(times)) * 1e6
+        out[name + "_pool_blocks"] = blocks
+    out["speedup_vs_isolated"] = out["isolated_us"] / out["shared_us"]
+    out["steps"] = n_steps
+    return out
+
+
+def pmc_probe(device, reps=3, mib=256):
+    """Plain copies of known size, so that traffic counters can be calibrated in the same run."""
+    import torch
+    from paper_2603_14371_amd import binding as B
+    n = mib << 20
+    src = torch.empty(n, dtype=torch.uint8, device=device).fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device=device)
+    stream = torch.cuda.current_stream(device).cuda_stream
+    for _ in range(reps):
+        B.oxy_copy_probe(dst.data_ptr(), src.data_ptr(), n, stream)
+    torch.cuda.synchronize(device)
+    return n
+
+
 def cpu_baseline(sample_layers=12):
     """The float64 oracle, as it stands, on one layer of a stress-shaped mixed step."""
     from oracle import attention
@@ -294,6 +354,9 @@ def main():
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-frame", action="store_true")
+    ap.add_argument("--no-cross-task", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="also launch plain 256 MiB copies (calibration of traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (sharding by prefix group is described in "
@@ -326,6 +389,18 @@ def main():
                      "launch_us": round(s["attn_launch_us"], 2),
                      "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
     }
+    out["step_us_with_events"] = round(s["step_us_with_events"], 2)
+    traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
+    if os.path.exists(traffic_file):
+        t = json.load(open(traffic_file))
+        out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
+        out["roofline"]["traffic_source"] = "profiles/pmc_traffic_stress.json (rocprofv3 --pmc " \
+                                            "FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size)"
+    if args.pmc_probe:
+        out["pmc_probe_bytes"] = pmc_probe(device)
+    if not args.no_cross_task:
+        out["cross_task"] = {k: round(v, 2) for k, v in
+                             bench_cross_task(device, args.split_tokens).items()}
     if not args.no_frame:
         out["pi05_frame"] = {k: round(v, 2) for k, v in bench_frame(device, args.split_tokens).items()}
     if not args.no_cpu:

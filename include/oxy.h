@@ -207,6 +207,11 @@ int32_t oxy_batch_slots(const oxy_batch *batch, int64_t *out, int32_t cap);
  * kv_begin, kv_end, causal base position (or 0x3fffffff), partial index, path. */
 int32_t oxy_batch_work(const oxy_batch *batch, int32_t *out, int32_t cap_items);
 
+/* Measurement aid: a plain 16-byte-per-lane device copy of `bytes` (multiple of 16) from src to
+ * dst (both DEVICE), enqueued on hip_stream.  It moves a known number of bytes, so hardware
+ * traffic counters read during it calibrate the same counters read during the attention launch. */
+int32_t oxy_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
+
 const char *oxy_last_error(void);
 int32_t oxy_version(void);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
-    "oxy_batch_slots", "oxy_batch_work",
+    "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe",
 ]
 
 
@@ -100,6 +100,7 @@ def lib():
             "oxy_batch_info": [vp, pi32, pi32, pi32, pi32],
             "oxy_batch_slots": [vp, ctypes.POINTER(ctypes.c_int64), i32],
             "oxy_batch_work": [vp, pi32, i32],
+            "oxy_copy_probe": [vp, vp, ctypes.c_size_t, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -300,3 +301,7 @@ def oxy_batch_work(batch):
     out = np.zeros((max(n, 1), 8), dtype=np.int32)
     _check(lib().oxy_batch_work(batch, _p32(out), n))
     return out[:n]
+
+
+def oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream):
+    _check(lib().oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream or None))

@@ -12,10 +12,12 @@ constexpr int kPage = 16;        // tokens per page
 constexpr int kPageBytes = kPage * kDim * 2;      // one K page or one V page (bf16)
 constexpr int kBlockBytes = 2 * kPageBytes;       // K page + V page of one layer
 constexpr int kNoCausal = 0x3fffffff;
-constexpr int kWorkWords = 8;
+constexpr int kWorkWords = 32;             // one 128-byte line per work record
+constexpr int kWorkInlineToks = 8;         // words 8..15: query token ids of the tile
+constexpr int kWorkInlinePages = 16;       // words 16..31: block ids of the first 16 pages
 constexpr int kMaxInlineBlocks = 512;             // block ids passed by value to append/gather
 
-// work record fields
+// work record fields (words 0..7)
 enum { W_TOK_OFF = 0, W_N_TOK, W_TBL_OFF, W_KV_BEGIN, W_KV_END, W_CAUSAL_Q0, W_PART_IDX, W_PATH };
 // paths
 enum { PATH_STREAM = 0,  // <=2 query tokens (16 rows): 4 wavefronts split the keys, KV to registers
@@ -53,5 +55,6 @@ struct AttnArgs {
   float scale;
 };
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 }  // namespace oxy

@@ -239,7 +239,15 @@ __device__ __forceinline__ u32x4 value_mask(const int left, const int g) {
 struct WorkItem {
   int tok_off, n_tok, kv_begin, kv_end, q0, part_idx;
   const int32_t* tbl;
+  int rec;   // this lane's word of the 32-word record (lanes 32..63 mirror 0..31)
 };
+
+// block ids of the split, one per lane: from the record's inline copy when the split has at
+// most 16 pages (no dependent load), else from the block table
+__device__ __forceinline__ int split_block_ids(const WorkItem& wi, const int lane, const int npg) {
+  if (npg <= kWorkInlinePages) return __shfl(wi.rec, 16 + (lane & 15));
+  return wi.tbl[(wi.kv_begin >> 4) + (lane < npg ? lane : 0)];
+}
 
 // ---- tile path: <= 8 query tokens (64 rows); the four wavefronts share every KV page through
 // LDS (double-buffered, one barrier per 32-key step) and own 16 rows each.
@@ -250,17 +258,9 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   const int ts = 2 * wv + (n >> 3), h = n & 7;
   const bool row_valid = ts < wi.n_tok;
   const bool wave_active = 2 * wv < wi.n_tok;
-  const int tok = row_valid ? a.tok_list[wi.tok_off + ts] : 0;
+  const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
   const int qpos = wi.q0 + ts;
   u32x4 qf[8];
-  {
-    const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const u32x4 z = {0, 0, 0, 0};
-      qf[j] = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
-    }
-  }
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
 #pragma unroll
@@ -274,9 +274,8 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   u32x4 st0[8], st1[8];
   // block ids of the whole split, one per lane (a split has at most 64 pages): fetched once,
   // then read with v_readlane, so no step waits on a scalar load before issuing its pages
-  const int pg0 = wi.kv_begin >> 4;
-  const int npg = ((wi.kv_end + 15) >> 4) - pg0;
-  const int ids = wi.tbl[pg0 + (lane < npg ? lane : 0)];
+  const int npg = ((wi.kv_end + 15) >> 4) - (wi.kv_begin >> 4);
+  const int ids = split_block_ids(wi, lane, npg);
   // Every fetch issues exactly eight loads and no fetch is conditional: the compiler counts
   // outstanding loads per control-flow path, and a conditional load would make it wait for
   // everything at the next join.  A step past the end re-reads one hot 4 KiB (eight times the
@@ -297,6 +296,29 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     st[5] = *(const u32x4*)(pa + o * (kPageBytes + 4096));
     st[6] = *(const u32x4*)(pb + o * kPageBytes);
     st[7] = *(const u32x4*)(pb + o * (kPageBytes + 4096));
+  };
+  // Values of keys beyond the split's end are zero-selected once, on their way into LDS (only
+  // the last step of a split can have any); the asm statement keeps this a real branch.
+  // Thread tid holds V chunks tid and tid+256 of each page: chunk ci = (c, gp, m) with gp =
+  // (ci >> 4) & 1, i.e. keys 4gp..4gp+3 and 8+4gp..8+4gp+3 of that page.
+  auto sanitize = [&](const int s, u32x4 (&st)[8]) {
+    const int left = wi.kv_end - (wi.kv_begin + 32 * s);
+    if (s < nsteps && left < 32) {
+      asm volatile("" ::: "memory");
+      const int gp = (tid >> 4) & 1;
+#pragma unroll
+      for (int pgi = 0; pgi < 2; ++pgi) {
+        const int k0 = 16 * pgi + 4 * gp;
+        u32x4 mask;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          mask[i] = (k0 + 2 * i < left ? 0xffffu : 0u) | (k0 + 2 * i + 1 < left ? 0xffff0000u : 0u);
+          mask[2 + i] = (k0 + 8 + 2 * i < left ? 0xffffu : 0u) | (k0 + 9 + 2 * i < left ? 0xffff0000u : 0u);
+        }
+        st[4 + 2 * pgi] &= mask;
+        st[5 + 2 * pgi] &= mask;
+      }
+    }
   };
   auto commit = [&](const int stage, const u32x4 (&st)[8]) {
     char* dst = smem + stage * kStageBytes + tid * 16;
@@ -325,19 +347,16 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     u32x4 pf, pl;
     softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
                  pf, pl);
-    const bool masked = left < 32;   // wave-uniform
-    const u32x4 mask = value_mask(left, g);
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      u32x4 v = *(const u32x4*)(sk + lds_v + c * 512);
-      if (masked) v &= mask;
+    for (int c = 0; c < 16; ++c) {   // V was sanitised on its way into LDS
+      const u32x4 v = *(const u32x4*)(sk + lds_v + c * 512);
       acc[c] = mfma16(v, pl, mfma16(v, pf, acc[c]));
     }
   };
   // body(s, cur, nxt): cur's content (step s) already sits in LDS, nxt holds step s+1 in
   // flight.  The scheduling barriers keep the order "issue s+2, compute s, then wait for s+1",
   // otherwise the wait would be hoisted above the compute.
-  auto body = [&](const int s, u32x4 (&cur)[8], const u32x4 (&nxt)[8]) {
+  auto body = [&](const int s, u32x4 (&cur)[8], u32x4 (&nxt)[8]) {
     if (s == 3) DBG_MARK(8);
     fetch(s + 2, cur);
     __builtin_amdgcn_sched_barrier(0);
@@ -345,6 +364,7 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     if (wave_active && s < nsteps) compute(s);
     __builtin_amdgcn_sched_barrier(0);
     if (s == 3) DBG_MARK(10);
+    sanitize(s + 1, nxt);
     commit((s + 1) & 1, nxt);
     if (s == 3) DBG_MARK(11);
     __syncthreads();
@@ -353,7 +373,16 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   DBG_MARK(1);
   fetch(0, st0);
   fetch(1, st1);
+  {  // the query rows come after the first pages are on their way (they are needed later)
+    const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const u32x4 z = {0, 0, 0, 0};
+      qf[j] = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);
+  sanitize(0, st0);
   commit(0, st0);
   __syncthreads();
   DBG_MARK(2);
@@ -386,7 +415,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const int n = lane & 15, g = lane >> 4;
   const int ts = n >> 3, h = n & 7;
   const bool row_valid = ts < wi.n_tok;
-  const int tok = row_valid ? a.tok_list[wi.tok_off + ts] : 0;
+  const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
   const int qpos = wi.q0 + ts;
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
@@ -397,9 +426,8 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const int nsteps = (wi.kv_end - wi.kv_begin + 31) >> 5;
 
   u32x4 kr[16], vr[16];   // kr[2j+hf]: K chunk of (j, hf); vr[c]: V chunk of block c
-  const int pg0 = wi.kv_begin >> 4;
-  const int npg = ((wi.kv_end + 15) >> 4) - pg0;
-  const int ids = wi.tbl[pg0 + (lane < npg ? lane : 0)];   // block ids of the split, one per lane
+  const int npg = ((wi.kv_end + 15) >> 4) - (wi.kv_begin >> 4);
+  const int ids = split_block_ids(wi, lane, npg);
   const int lane_k = (g * 8 + (n & 7)) * 16;
   const int lane_v = kPageBytes + ((g & 1) * 16 + n) * 16;
   // Always sixteen loads per call and no conditional call (see tile_path): a step past the end
@@ -458,7 +486,8 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     __builtin_amdgcn_sched_barrier(0);  // the next K pages reuse kr[]: issue only after S
     load_k(s + 4);
     __builtin_amdgcn_sched_barrier(0);
-    if (left < 32) {   // wave-uniform; only the last step of a split
+    if (left < 32) {   // wave-uniform; only the last step of a split (asm: keep it a branch)
+      asm volatile("" ::: "memory");
       const u32x4 mask = value_mask(left, g);
 #pragma unroll
       for (int c = 0; c < 16; ++c) vr[c] &= mask;
@@ -483,6 +512,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   }
   __syncthreads();
   const int r = tid >> 4, seg = (tid & 15) * 16;
+  const int otok = __shfl(wi.rec, 8 + (r >> 3));
   if ((r >> 3) < wi.n_tok) {
     const float ninf = -__builtin_inff();
     float big = ninf;
@@ -494,7 +524,6 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       wgt[w] = (sml[w][r][0] == ninf) ? 0.f : fast_exp2(sml[w][r][0] - big);
       total = __builtin_fmaf(wgt[w], sml[w][r][1], total);
     }
-    const int otok = a.tok_list[wi.tok_off + (r >> 3)];
     const size_t slot = (size_t)a.part_off[otok] + wi.part_idx;
     float* dst = a.part_acc + (slot * kHeads + (r & 7)) * kDim + seg;
 #pragma unroll
@@ -519,16 +548,17 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   __shared__ __align__(16) char smem[kSmemBytes];
   __shared__ float sml[4][16][2];
   __shared__ __align__(16) char qs[16 * kDim * 2];
-  const int32_t* __restrict__ w = a.work + (size_t)blockIdx.x * kWorkWords;
+  // one 128-byte load brings the whole record; its fields are read out lane-wise
   WorkItem wi;
-  wi.tok_off = w[W_TOK_OFF];
-  wi.n_tok = w[W_N_TOK];
-  wi.tbl = a.tables + w[W_TBL_OFF];
-  wi.kv_begin = w[W_KV_BEGIN];
-  wi.kv_end = w[W_KV_END];
-  wi.q0 = w[W_CAUSAL_Q0];
-  wi.part_idx = w[W_PART_IDX];
-  const int path = w[W_PATH];
+  wi.rec = a.work[(size_t)blockIdx.x * kWorkWords + (threadIdx.x & 31)];
+  wi.tok_off = __builtin_amdgcn_readlane(wi.rec, W_TOK_OFF);
+  wi.n_tok = __builtin_amdgcn_readlane(wi.rec, W_N_TOK);
+  wi.tbl = a.tables + __builtin_amdgcn_readlane(wi.rec, W_TBL_OFF);
+  wi.kv_begin = __builtin_amdgcn_readlane(wi.rec, W_KV_BEGIN);
+  wi.kv_end = __builtin_amdgcn_readlane(wi.rec, W_KV_END);
+  wi.q0 = __builtin_amdgcn_readlane(wi.rec, W_CAUSAL_Q0);
+  wi.part_idx = __builtin_amdgcn_readlane(wi.rec, W_PART_IDX);
+  const int path = __builtin_amdgcn_readlane(wi.rec, W_PATH);
   DBG_MARK(0);
   if (path == PATH_TILE) {
     __builtin_amdgcn_s_setprio(2);   // compute-heavy: issue ahead of co-resident streaming waves
@@ -556,8 +586,13 @@ extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
 
 // ------------------------------------------------------------------------------------------
 // merge of a query token's partials (log-sum-exp rule).  Two workgroups per token (four heads
-// each); a thread owns four consecutive output dims of one head and walks the token's
-// partials with independent 16-byte loads.
+// each); a thread owns four consecutive output dims of one head.  The accumulator loads of the
+// first eight partials are issued before anything else, the (m, l) pairs go through LDS.
+// (A merge fused into attn_kernel by "last arriver merges" was built twice and measured: with
+// device-scope fences every workgroup pays a whole-L2 write-back + invalidate (165 us per
+// launch); with scoped write-through stores and no fences it is correct and fence-free, but the
+// tile workgroups finish last and then merge their eight tokens serially (53 us).  Hence its own
+// kernel.)
 // ------------------------------------------------------------------------------------------
 constexpr int kMergeChunk = 32;   // partials whose (m, l) are staged at once
 
@@ -570,49 +605,51 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) {
   const size_t base = (size_t)a.part_off[tok];
   const float* ml = a.part_ml + (base * kHeads + ((blockIdx.x & 1) << 2)) * 2;
   const float* src = a.part_acc + (base * kHeads + h) * kDim + d0;
-  // reference max over all partials first (the (m, l) pairs are tiny: one load per thread)
-  float big = -__builtin_inff();
-  for (int p0 = 0; p0 < np; p0 += 32) {
-    const int p = p0 + (t >> 3), e = t & 7;      // 32 partials x 4 heads x (m, l) per pass
-    float v = -__builtin_inff();
-    if (p < np && !(e & 1)) v = ml[(size_t)p * kHeads * 2 + e];
-    // heads are e >> 1; keep only this thread's head when reducing
-    s_ml[t >> 3][e >> 1][e & 1] = v;
+  const size_t stride = (size_t)kHeads * kDim;
+  const float ninf = -__builtin_inff();
+  // first eight accumulator rows on their way before the (m, l) staging round trip
+  f32x4 x[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) x[u] = *(const f32x4*)(src + (size_t)(u < np ? u : 0) * stride);
+  auto stage = [&](const int p0) {
+    const int p = p0 + (t >> 3), e = t & 7;
+    s_ml[t >> 3][e >> 1][e & 1] = (p < np) ? ml[(size_t)p * kHeads * 2 + e] : ((e & 1) ? 0.f : ninf);
     __syncthreads();
-    for (int q = 0; q < 32 && p0 + q < np; ++q) big = fmaxf(big, s_ml[q][hw][0]);
-    __syncthreads();
+  };
+  float big = ninf;
+  for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
+    if (p0) __syncthreads();
+    stage(p0);
+    for (int q = 0; q < kMergeChunk && p0 + q < np; ++q) big = fmaxf(big, s_ml[q][hw][0]);
   }
   float total = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  auto add = [&](const int q, const f32x4& v) {
+    const float mp = s_ml[q][hw][0];
+    const float wgt = (mp == ninf) ? 0.f : fast_exp2(mp - big);
+    total = __builtin_fmaf(wgt, s_ml[q][hw][1], total);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, v[e], o[e]);
+  };
   for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
+    if (np > kMergeChunk) {          // otherwise the first staging is still in place
+      __syncthreads();
+      stage(p0);
+    }
     const int cnt = min(kMergeChunk, np - p0);
-    {
-      const int p = p0 + (t >> 3), e = t & 7;
-      s_ml[t >> 3][e >> 1][e & 1] = (p < np) ? ml[(size_t)p * kHeads * 2 + e] : 0.f;
-    }
-    __syncthreads();
-    const float* sp = src + (size_t)p0 * kHeads * kDim;
+    const float* sp = src + (size_t)p0 * stride;
     int q = 0;
-    for (; q + 8 <= cnt; q += 8) {               // eight independent 16-byte loads in flight
-      f32x4 x[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) x[u] = *(const f32x4*)(sp + (size_t)(q + u) * kHeads * kDim);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float wgt = fast_exp2(s_ml[q + u][hw][0] - big);
-        total = __builtin_fmaf(wgt, s_ml[q + u][hw][1], total);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, x[u][e], o[e]);
-      }
+    if (p0 == 0) {                   // the prefetched rows
+      for (; q < 8 && q < cnt; ++q) add(q, x[q]);
     }
-    for (; q < cnt; ++q) {
-      const f32x4 x = *(const f32x4*)(sp + (size_t)q * kHeads * kDim);
-      const float wgt = fast_exp2(s_ml[q][hw][0] - big);
-      total = __builtin_fmaf(wgt, s_ml[q][hw][1], total);
+    for (; q + 8 <= cnt; q += 8) {
+      f32x4 y[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, x[e], o[e]);
+      for (int u = 0; u < 8; ++u) y[u] = *(const f32x4*)(sp + (size_t)(q + u) * stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) add(q + u, y[u]);
     }
-    __syncthreads();
+    for (; q < cnt; ++q) add(q, *(const f32x4*)(sp + (size_t)q * stride));
   }
   const float inv = 1.f / total;
   typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
@@ -628,6 +665,21 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// plain copy of known size (calibration of traffic counters)
+__global__ __launch_bounds__(256) void copy_probe_kernel(u32x4* __restrict__ dst,
+                                                         const u32x4* __restrict__ src, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+    dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  const size_t want = (n16 + 255) / 256;
+  copy_probe_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>((u32x4*)dst, (const u32x4*)src, n16);
   return hipGetLastError();
 }
 

@@ -427,7 +427,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     auto add_work = [&](int32_t tok_off, int32_t n_tok, int32_t tbl_off, int32_t b, int32_t e,
                         int32_t q0, int32_t part, int32_t path) {
       int32_t w[oxy::kWorkWords] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
-      work.insert(work.end(), w, w + oxy::kWorkWords);
+      work.insert(work.end(), w, w + oxy::kWorkWords);   // words 8.. are filled after commit
     };
     // Which path evaluates a query depends on its item only (kind, n_new, phase), never on its
     // batch mates, so an item's arithmetic is the same in every batch it can appear in:
@@ -543,7 +543,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       }
       std::vector<int32_t> sorted;
       sorted.reserve(longest * kXcd * oxy::kWorkWords);
-      const int32_t noop[oxy::kWorkWords] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
+      int32_t noop[oxy::kWorkWords] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
       size_t last_real = 0;
       for (size_t k = 0; k < longest; ++k)
         for (int x = 0; x < kXcd; ++x) {
@@ -603,6 +603,19 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   for (const TableRef& tr : table_refs) {
     if ((int32_t)tables.size() < tr.off + tr.count) tables.resize(tr.off + tr.count);
     std::copy(tr.src->begin(), tr.src->begin() + tr.count, tables.begin() + tr.off);
+  }
+
+  // ---- inline copies in every work record: its token ids and the block ids of its first pages,
+  // so a workgroup needs one 128-byte load before it can issue its first pages
+  for (size_t r = 0; r + oxy::kWorkWords <= work.size(); r += oxy::kWorkWords) {
+    int32_t* w = &work[r];
+    if (w[oxy::W_PATH] == oxy::PATH_NOOP) continue;
+    for (int32_t i = 0; i < oxy::kWorkInlineToks; ++i)
+      w[8 + i] = toks[w[oxy::W_TOK_OFF] + std::min(i, w[oxy::W_N_TOK] - 1)];
+    const int32_t pg0 = w[oxy::W_KV_BEGIN] / kPage;
+    const int32_t npg = blocks_for(w[oxy::W_KV_END]) - pg0;
+    for (int32_t i = 0; i < oxy::kWorkInlinePages; ++i)
+      w[16 + i] = tables[w[oxy::W_TBL_OFF] + pg0 + std::min(i, npg - 1)];
   }
 
   // ---- descriptor image
@@ -752,6 +765,13 @@ int32_t oxy_gather_kv(oxy_pool* p, int32_t layer, const int64_t* slots, int32_t 
   return OXY_OK;
 }
 
+int32_t oxy_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src || (bytes & 15)) return fail(OXY_ERR_INVALID_ARG, "copy_probe: null or bytes % 16");
+  hipError_t e = oxy::launch_copy_probe(dst, src, bytes, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "copy_probe: launch");
+  return OXY_OK;
+}
+
 // ---- introspection ------------------------------------------------------------------------
 int32_t oxy_stream_info(oxy_pool* p, int32_t sid, int32_t* prefix_id, int32_t* kind,
                         int32_t* own_len, int32_t* n_blocks) {
@@ -834,8 +854,9 @@ int32_t oxy_batch_slots(const oxy_batch* b, int64_t* out, int32_t cap) {
 
 int32_t oxy_batch_work(const oxy_batch* b, int32_t* out, int32_t cap_items) {
   if (!b || !out || cap_items < b->n_work) return fail(OXY_ERR_INVALID_ARG, "batch_work: cap");
-  std::copy(b->host.begin() + b->off_work,
-            b->host.begin() + b->off_work + (size_t)b->n_work * oxy::kWorkWords, out);
+  for (int32_t i = 0; i < b->n_work; ++i)   // the eight header words of each record
+    std::copy(b->host.begin() + b->off_work + (size_t)i * oxy::kWorkWords,
+              b->host.begin() + b->off_work + (size_t)i * oxy::kWorkWords + 8, out + (size_t)i * 8);
   return OXY_OK;
 }
 
