@@ -99,19 +99,24 @@ class StepRunner:
 
 
 class EventSet:
-    """2*L timing events per step, handed to the library as raw handles."""
+    """3*L timing events per step (before the work-item kernel, after it, after the merge),
+    handed to the library as raw handles."""
 
     def __init__(self, n_layers):
         import ctypes
         import torch
-        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_layers)]
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n_layers)]
         for e in self.ev:
             e.record()          # creates the underlying hipEvent_t
         self.raw = (ctypes.c_void_p * len(self.ev))(*[e.cuda_event for e in self.ev])
 
-    def attention_us(self):
-        return [self.ev[2 * i].elapsed_time(self.ev[2 * i + 1]) * 1e3
-                for i in range(len(self.ev) // 2)]
+    def work_us(self):
+        return [self.ev[3 * i].elapsed_time(self.ev[3 * i + 1]) * 1e3
+                for i in range(len(self.ev) // 3)]
+
+    def merge_us(self):
+        return [self.ev[3 * i + 1].elapsed_time(self.ev[3 * i + 2]) * 1e3
+                for i in range(len(self.ev) // 3)]
 
 
 def _live_kv_tokens(gw, items):
@@ -162,8 +167,9 @@ def bench_stress(args, device):
         runner.step(steps[args.warmup + args.steps + i]["items"], sets[i].raw)
     torch.cuda.synchronize(device)
     step_us_ev = (time.perf_counter() - t_start) / args.steps * 1e6
-    attn_us = [t for es in sets for t in es.attention_us()]
+    attn_us = [t for es in sets for t in es.work_us()]
     attn_avg_us = float(np.mean(attn_us))
+    merge_avg_us = float(np.mean([t for es in sets for t in es.merge_us()]))
     # every step appends one token per decode stream: unique KV tokens of the instrumented steps
     kv_tokens = kv0 + n_decode * (args.steps + (args.steps - 1) / 2.0)
     alg_bytes = kv_tokens * TOKEN_BYTES + n_tok * QO_BYTES
@@ -172,6 +178,7 @@ def bench_stress(args, device):
         "step_us": step_us,
         "step_us_with_events": step_us_ev,
         "attn_launch_us": attn_avg_us,
+        "merge_launch_us": merge_avg_us,
         "alg_bytes_per_launch": alg_bytes,
         "kv_gbps": achieved,
         "decode_tokens_per_s": n_decode / (step_us * 1e-6),
@@ -385,8 +392,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(s["kv_gbps"], 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(s["kv_gbps"] / HBM_PEAK_GBPS, 4),
                      "traffic": None,
-                     "kernel": "mixed attention launch (work items + merge), per layer",
+                     "kernel": "attn_kernel (all work items of one layer)",
                      "launch_us": round(s["attn_launch_us"], 2),
+                     "merge_launch_us": round(s["merge_launch_us"], 2),
                      "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
     }
     out["step_us_with_events"] = round(s["step_us_with_events"], 2)

@@ -171,12 +171,13 @@ int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t laye
                             const void *q, void *out, float *lse, float scale,
                             void *hip_stream);
 /* All layers [layer_begin, layer_end) of one step, in order: for each layer the append and
- * then the mixed attention, exactly as the two calls above would enqueue them (this is their
- * loop moved below the ABI, so a caller pays one call per step instead of two per layer).
+ * then the mixed attention, with the same kernels and the same effects as the two calls above
+ * (this is their loop moved below the ABI: one call per step instead of two per layer, and the
+ * merge of layer l shares its launch with the append of layer l+1, which touch disjoint memory).
  * Layer l uses k_new + l*kv_layer_stride, v_new + l*kv_layer_stride (bytes), q + l*q_layer_stride,
  * out + l*q_layer_stride, and lse + l*lse_layer_stride (bytes) when lse is not NULL.
- * events: NULL, or HOST array of 2*(layer_end-layer_begin) hipEvent_t recorded on hip_stream
- * immediately before and after each layer's attention launch (a profiling hook). */
+ * events: NULL, or HOST array of 3*(layer_end-layer_begin) hipEvent_t recorded on hip_stream per
+ * layer: before the work-item kernel, after it, and after the merge (a profiling hook). */
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,
                         size_t kv_layer_stride, const void *q, void *out, size_t q_layer_stride,

@@ -54,7 +54,17 @@ struct AttnArgs {
   int32_t n_q;
   float scale;
 };
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);       // work items, then merge
+hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s);  // work items only
+struct AppendArgs {
+  const void* k_new;
+  const void* v_new;
+  const int32_t* d_slots;
+  int32_t n_tokens;
+  void* layer_base;
+};
+// merge of `a`, and in the same launch the append described by `next` (may be null)
+hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s);
 hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 }  // namespace oxy

@@ -586,71 +586,52 @@ extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
 
 // ------------------------------------------------------------------------------------------
 // merge of a query token's partials (log-sum-exp rule).  Two workgroups per token (four heads
-// each); a thread owns four consecutive output dims of one head.  The accumulator loads of the
-// first eight partials are issued before anything else, the (m, l) pairs go through LDS.
+// each); a thread owns four consecutive output dims of one head and has every load of the first
+// sixteen partials in flight at once.
 // (A merge fused into attn_kernel by "last arriver merges" was built twice and measured: with
 // device-scope fences every workgroup pays a whole-L2 write-back + invalidate (165 us per
 // launch); with scoped write-through stores and no fences it is correct and fence-free, but the
 // tile workgroups finish last and then merge their eight tokens serially (53 us).  Hence its own
 // kernel.)
 // ------------------------------------------------------------------------------------------
-constexpr int kMergeChunk = 32;   // partials whose (m, l) are staged at once
+constexpr int kMergeAhead = 16;   // partials whose loads are all issued before anything is used
 
-__global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) {
-  __shared__ float s_ml[kMergeChunk][4][2];
-  const int tok = blockIdx.x >> 1, t = threadIdx.x;
-  const int hw = t >> 6;                         // head within this workgroup's four
-  const int h = ((blockIdx.x & 1) << 2) | hw, d0 = (t & 63) * 4;
+__device__ __forceinline__ void merge_block(const AttnArgs& a, const int block) {
+  const int tok = block >> 1, t = threadIdx.x;
+  const int h = ((block & 1) << 2) | (t >> 6), d0 = (t & 63) * 4;
   const int np = a.n_parts[tok];
   const size_t base = (size_t)a.part_off[tok];
-  const float* ml = a.part_ml + (base * kHeads + ((blockIdx.x & 1) << 2)) * 2;
+  typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+  const float* ml = a.part_ml + (base * kHeads + h) * 2;
   const float* src = a.part_acc + (base * kHeads + h) * kDim + d0;
   const size_t stride = (size_t)kHeads * kDim;
   const float ninf = -__builtin_inff();
-  // first eight accumulator rows on their way before the (m, l) staging round trip
-  f32x4 x[8];
+  // one round trip for the common case: every load of the first 16 partials is in flight at once
+  f32x4 x[kMergeAhead];
+  f32x2 w[kMergeAhead];
 #pragma unroll
-  for (int u = 0; u < 8; ++u) x[u] = *(const f32x4*)(src + (size_t)(u < np ? u : 0) * stride);
-  auto stage = [&](const int p0) {
-    const int p = p0 + (t >> 3), e = t & 7;
-    s_ml[t >> 3][e >> 1][e & 1] = (p < np) ? ml[(size_t)p * kHeads * 2 + e] : ((e & 1) ? 0.f : ninf);
-    __syncthreads();
-  };
-  float big = ninf;
-  for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
-    if (p0) __syncthreads();
-    stage(p0);
-    for (int q = 0; q < kMergeChunk && p0 + q < np; ++q) big = fmaxf(big, s_ml[q][hw][0]);
+  for (int u = 0; u < kMergeAhead; ++u) {
+    const int p = u < np ? u : 0;
+    x[u] = *(const f32x4*)(src + (size_t)p * stride);
+    w[u] = *(const f32x2*)(ml + (size_t)p * kHeads * 2);
   }
+  float big = ninf;
+#pragma unroll
+  for (int u = 0; u < kMergeAhead; ++u) big = fmaxf(big, u < np ? w[u][0] : ninf);
+  for (int p = kMergeAhead; p < np; ++p) big = fmaxf(big, ml[(size_t)p * kHeads * 2]);
   float total = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  auto add = [&](const int q, const f32x4& v) {
-    const float mp = s_ml[q][hw][0];
+  auto add = [&](const float mp, const float lp, const f32x4& v) {
     const float wgt = (mp == ninf) ? 0.f : fast_exp2(mp - big);
-    total = __builtin_fmaf(wgt, s_ml[q][hw][1], total);
+    total = __builtin_fmaf(wgt, lp, total);
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, v[e], o[e]);
   };
-  for (int p0 = 0; p0 < np; p0 += kMergeChunk) {
-    if (np > kMergeChunk) {          // otherwise the first staging is still in place
-      __syncthreads();
-      stage(p0);
-    }
-    const int cnt = min(kMergeChunk, np - p0);
-    const float* sp = src + (size_t)p0 * stride;
-    int q = 0;
-    if (p0 == 0) {                   // the prefetched rows
-      for (; q < 8 && q < cnt; ++q) add(q, x[q]);
-    }
-    for (; q + 8 <= cnt; q += 8) {
-      f32x4 y[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) y[u] = *(const f32x4*)(sp + (size_t)(q + u) * stride);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) add(q + u, y[u]);
-    }
-    for (; q < cnt; ++q) add(q, *(const f32x4*)(sp + (size_t)q * stride));
-  }
+  for (int u = 0; u < kMergeAhead; ++u)
+    if (u < np) add(w[u][0], w[u][1], x[u]);
+  for (int p = kMergeAhead; p < np; ++p)
+    add(ml[(size_t)p * kHeads * 2], ml[(size_t)p * kHeads * 2 + 1], *(const f32x4*)(src + (size_t)p * stride));
   const float inv = 1.f / total;
   typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
   const u32x2 packed = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
@@ -659,13 +640,41 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) {
     a.lse[(size_t)tok * kHeads + h] = (big + __builtin_amdgcn_logf(total)) * 0.6931471805599453f;
 }
 
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+__global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) { merge_block(a, blockIdx.x); }
+
+// merge of one layer and, in the same launch, the append of the next layer's new rows (the two
+// touch disjoint memory: partials/outputs of layer l, pool slots of layer l+1)
+__global__ __launch_bounds__(256) void merge_append_kernel(const AttnArgs a, const AppendArgs nx) {
+  const int n_merge = 2 * a.n_q;
+  if ((int)blockIdx.x < n_merge) {
+    merge_block(a, blockIdx.x);
+  } else {
+    const int tok = blockIdx.x - n_merge;
+    append_row((const uint16_t*)nx.k_new + (size_t)tok * kDim,
+               (const uint16_t*)nx.v_new + (size_t)tok * kDim, nx.d_slots[tok],
+               (char*)nx.layer_base, threadIdx.x);
+  }
+}
+
+hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s) {
   if (a.n_work <= 0 || a.n_q <= 0) return hipErrorInvalidValue;
   attn_kernel<<<a.n_work, 256, 0, s>>>(a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
   return hipGetLastError();
+}
+
+hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s) {
+  if (a.n_q <= 0) return hipErrorInvalidValue;
+  if (next && next->n_tokens > 0)
+    merge_append_kernel<<<2 * a.n_q + next->n_tokens, 256, 0, s>>>(a, *next);
+  else
+    merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+  hipError_t e = launch_attention_work(a, s);
+  if (e != hipSuccess) return e;
+  return launch_merge_append(a, nullptr, s);
 }
 
 // plain copy of known size (calibration of traffic counters)

@@ -685,13 +685,9 @@ int32_t oxy_stream_append(oxy_pool* p, const oxy_batch* b, int32_t layer, const 
   return OXY_OK;
 }
 
-int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* q,
-                            void* out, float* lse, float scale, void* hip_stream) {
-  if (!p || !b || b->pool != p || !q || !out || p->host_only)
-    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: null argument, foreign batch or host-only pool");
-  if (layer < 0 || layer >= p->cfg.n_layers) return fail(OXY_ERR_INVALID_ARG, "mixed_attention: layer %d", layer);
-  if (b->flags & OXY_BATCH_APPEND_ONLY)
-    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: batch was built append-only");
+namespace {
+oxy::AttnArgs attn_args(const oxy_pool* p, const oxy_batch* b, int32_t layer, const void* q, void* out,
+                        float* lse, float scale) {
   const DescSlot& ds = p->slots[b->slot];
   const int32_t* d = (const int32_t*)ds.d_base;
   oxy::AttnArgs a;
@@ -709,7 +705,19 @@ int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, cons
   a.n_work = b->n_work;
   a.n_q = b->n_tokens;
   a.scale = scale;
-  hipError_t e = oxy::launch_attention(a, (hipStream_t)hip_stream);
+  return a;
+}
+}  // namespace
+
+int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* q,
+                            void* out, float* lse, float scale, void* hip_stream) {
+  if (!p || !b || b->pool != p || !q || !out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: null argument, foreign batch or host-only pool");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(OXY_ERR_INVALID_ARG, "mixed_attention: layer %d", layer);
+  if (b->flags & OXY_BATCH_APPEND_ONLY)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention: batch was built append-only");
+  hipError_t e = oxy::launch_attention(attn_args(p, b, layer, q, out, lse, scale),
+                                       (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e, "mixed_attention: launch");
   return OXY_OK;
 }
@@ -719,26 +727,53 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
                         const void* q, void* out, size_t q_layer_stride, float* lse,
                         size_t lse_layer_stride, float scale, void* const* events,
                         void* hip_stream) {
-  if (!p || layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
+  if (!p || !b || b->pool != p || !k_new || !v_new || !q || !out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: null argument, foreign batch or host-only pool");
+  if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
     return fail(OXY_ERR_INVALID_ARG, "step_layers: layers [%d, %d)", layer_begin, layer_end);
+  if (b->flags & OXY_BATCH_APPEND_ONLY)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: batch was built append-only");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int32_t* d_desc = (const int32_t*)p->slots[b->slot].d_base;
+  auto append_of = [&](int32_t layer) {
+    oxy::AppendArgs ap;
+    ap.k_new = (const char*)k_new + (size_t)layer * kv_layer_stride;
+    ap.v_new = (const char*)v_new + (size_t)layer * kv_layer_stride;
+    ap.d_slots = d_desc + b->off_slots;
+    ap.n_tokens = b->n_tokens;
+    ap.layer_base = layer_base(p, layer);
+    return ap;
+  };
+  // Same kernels and the same order of effects as the per-layer calls; the merge of layer l and
+  // the append of layer l+1 (disjoint memory) share one launch.
+  {
+    oxy::AppendArgs first = append_of(layer_begin);
+    hipError_t e = oxy::launch_append(first.k_new, first.v_new, first.d_slots, first.n_tokens,
+                                      first.layer_base, s);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: append");
+  }
   for (int32_t layer = layer_begin; layer < layer_end; ++layer) {
     const size_t i = (size_t)(layer - layer_begin);
-    int32_t rc = oxy_stream_append(p, b, layer, (const char*)k_new + (size_t)layer * kv_layer_stride,
-                                   (const char*)v_new + (size_t)layer * kv_layer_stride, hip_stream);
-    if (rc != OXY_OK) return rc;
-    if (events) {
-      hipError_t e = hipEventRecord((hipEvent_t)events[2 * i], (hipStream_t)hip_stream);
-      if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    hipError_t e = hipSuccess;
+    if (events) e = hipEventRecord((hipEvent_t)events[3 * i], s);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    oxy::AttnArgs a = attn_args(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
+                                (char*)out + (size_t)layer * q_layer_stride,
+                                lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
+                                scale);
+    e = oxy::launch_attention_work(a, s);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: attention");
+    if (events) e = hipEventRecord((hipEvent_t)events[3 * i + 1], s);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    if (layer + 1 < layer_end) {
+      oxy::AppendArgs nx = append_of(layer + 1);
+      e = oxy::launch_merge_append(a, &nx, s);
+    } else {
+      e = oxy::launch_merge_append(a, nullptr, s);
     }
-    rc = oxy_mixed_attention(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
-                             (char*)out + (size_t)layer * q_layer_stride,
-                             lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
-                             scale, hip_stream);
-    if (rc != OXY_OK) return rc;
-    if (events) {
-      hipError_t e = hipEventRecord((hipEvent_t)events[2 * i + 1], (hipStream_t)hip_stream);
-      if (e != hipSuccess) return hip_fail(e, "step_layers: event");
-    }
+    if (e != hipSuccess) return hip_fail(e, "step_layers: merge");
+    if (events) e = hipEventRecord((hipEvent_t)events[3 * i + 2], s);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
   }
   return OXY_OK;
 }
