@@ -29,15 +29,15 @@ TOKEN_BYTES = 1024          # K + V of one token in one layer: 2 * 256 * 2 B
 QO_BYTES = 2 * 8 * 256 * 2  # one query token read + one output token written
 
 
-def _build_state(workload, device, split_tokens):
+def _build_state(workload, device, split_tokens, stream_split_tokens=0):
     """Replays the set-up part of a trace (everything before its first attended step) with
     random resident data; returns the world and the remaining steps."""
     import torch
     from paper_2603_14371_amd import binding as B
     from paper_2603_14371_amd.harness import GpuWorld
     w = workload
-    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False,
-                  max_partials=8192)
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens,
+                  stream_split_tokens=stream_split_tokens, want_lse=False, max_partials=16384)
     gen = torch.Generator(device=device)
     gen.manual_seed(w["seed"])
     L = w["n_layers"]
@@ -138,7 +138,7 @@ def bench_stress(args, device):
     from paper_2603_14371_amd import synth
     w = synth.stress(mixed_steps=args.warmup + 2 * args.steps + 2)
     t0 = time.time()
-    gw, rest = _build_state(w, device, args.split_tokens)
+    gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens)
     setup_s = time.time() - t0
     steps = [op for op in rest if op["op"] == "step"]
     items = steps[0]["items"]
@@ -359,9 +359,12 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--stream-split-tokens", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-frame", action="store_true")
     ap.add_argument("--no-cross-task", action="store_true")
+    ap.add_argument("--only-frame", action="store_true",
+                    help="profiling aid: run only the pi0.5-shaped frame section")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="also launch plain 256 MiB copies (calibration of traffic counters)")
     args = ap.parse_args()
@@ -374,6 +377,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     device = torch.device("cuda:0")
+    if args.only_frame:
+        print(json.dumps({"pi05_frame": bench_frame(device, args.split_tokens)}))
+        return
     s = bench_stress(args, device)
     out = {
         "metric": "mixed action+decode attention step us (18 layers: append + attention)",

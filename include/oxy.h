@@ -111,11 +111,12 @@ typedef struct {
   int32_t max_work_items;   /* attention work items per batch (0 -> 16384)                   */
   int32_t max_partials;     /* per-token split results per batch (0 -> 32*max_q_tokens)      */
   int32_t split_tokens;     /* KV tokens per work item of the shared-tile path (prefix phase, action
-                               chunks), multiple of 32, <= 1024 (0 -> 256)                   */
+                               chunks), multiple of 32, <= 1024.  0 -> chosen from the length of
+                               the KV source alone: about an eighth of it, within [64, 256]      */
   int32_t stream_split_tokens; /* KV tokens per work item of the decode streaming path, multiple
-                               of 32, <= 1024 (0 -> split_tokens).  Both are
-                               fixed per pool so an item's arithmetic never depends on its
-                               batch mates                                                   */
+                               of 32, <= 1024 (0 -> split_tokens, or 256 if that is 0).  Both depend
+                               only on the pool and the item, so an item's arithmetic never
+                               depends on its batch mates                                    */
   int32_t flags;
 } oxy_pool_config;
 

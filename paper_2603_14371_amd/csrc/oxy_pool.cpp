@@ -105,11 +105,13 @@ bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
   if (c->max_append_tokens == 0) c->max_append_tokens = kPage * c->num_blocks;
   if (c->max_work_items == 0) c->max_work_items = 16384;
   if (c->max_partials == 0) c->max_partials = 32 * c->max_q_tokens;
-  if (c->split_tokens == 0) c->split_tokens = 256;
-  if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens;
+  // split_tokens == 0 stays 0: the tile path then sizes its splits from the length of the KV
+  // source alone (see tile_split_for), which keeps an item's arithmetic independent of its batch
+  if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens ? c->split_tokens : 256;
   if (c->max_live_batches < 1 || c->max_live_batches > 64 || c->max_q_tokens < 1 ||
       c->max_append_tokens < 1 || c->max_work_items < 1 || c->max_partials < 1 ||
-      c->split_tokens < 32 || c->split_tokens % 32 != 0 || c->split_tokens > 1024 ||
+      (c->split_tokens != 0 && (c->split_tokens < 32 || c->split_tokens % 32 != 0)) ||
+      c->split_tokens > 1024 ||
       c->stream_split_tokens < 32 || c->stream_split_tokens % 32 != 0 ||
       c->stream_split_tokens > 1024)
     return false;
@@ -141,6 +143,16 @@ void maybe_drop_prefix(oxy_pool* p, int32_t pid) {
   auto it = p->prefixes.find(pid);
   if (it != p->prefixes.end() && !it->second.handle && it->second.n_streams == 0)
     p->prefixes.erase(it);
+}
+
+// Split size of the shared-tile path for a KV source of `len` tokens.  With a configured
+// split_tokens it is that; otherwise about an eighth of the source, between 64 and 256 tokens:
+// short sources (an 832-token prefix, a 50-token chunk) get short dependent chains per
+// workgroup, long ones (2048 tokens) keep the number of partials per query down.
+int32_t tile_split_for(const oxy_pool_config& c, int32_t len) {
+  if (c.split_tokens) return c.split_tokens;
+  int32_t s = ((len + 7) / 8 + 31) / 32 * 32;
+  return std::max(64, std::min(256, s));
 }
 
 char* layer_base(const oxy_pool* p, int32_t layer) {
@@ -413,7 +425,6 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
                 (long long)n_tokens, c.max_q_tokens);
 
   // ---- work list on the lengths the step will have (state still untouched)
-  const int32_t split = c.split_tokens;
   std::vector<int32_t> work, toks, tables, n_parts(append_only ? 0 : n_tokens, 0);
   std::vector<int32_t> tbl_lens;  // (offset, count) pairs to fill after allocation
   struct TableRef {
@@ -451,6 +462,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       int32_t tbl_off = tbl_words;
       table_refs.push_back({tbl_off, &px.blocks, blocks_for(px.len)});
       tbl_words += blocks_for(px.len);
+      const int32_t split = tile_split_for(c, px.len);
       int32_t nsplit = (px.len + split - 1) / split;
       for (size_t t0 = 0; t0 < gt.size(); t0 += tile_tok) {
         int32_t n = (int32_t)std::min<size_t>(tile_tok, gt.size() - t0);
@@ -470,7 +482,8 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       bool causal = pl.s->kind == OXY_KIND_DECODE;
       const int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
-      const int32_t split = n_new <= 2 ? c.stream_split_tokens : c.split_tokens;
+      const int32_t split = n_new <= 2 ? c.stream_split_tokens
+                                       : tile_split_for(c, pl.new_len);
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
         int32_t n = std::min(step_tok, n_new - t0);
         int32_t tok_off = (int32_t)toks.size();
