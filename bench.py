@@ -86,15 +86,17 @@ class StepRunner:
         self.stream = torch.cuda.current_stream(device).cuda_stream
         self.n_tok = n_tok
 
-    def step(self, items, events=None):
+    def step(self, items, events=None, fuse=False):
         """One whole step: batch build, then append + attention for every layer (the per-layer
-        loop runs below the ABI in oxy_step_layers)."""
+        loop runs below the ABI in oxy_step_layers).  fuse: let the merge of layer l share a
+        launch with the append of layer l+1 (all layers' K/V are resident here)."""
         from paper_2603_14371_amd import binding as B
         gw = self.gw
         batch = B.oxy_batch_build(gw.pool, items, 0, self.stream)
         B.oxy_step_layers(gw.pool, batch, 0, self.L, self.k.data_ptr(), self.v.data_ptr(),
                           self.k.stride(0) * 2, self.q.data_ptr(), self.o.data_ptr(),
-                          self.q.stride(0) * 2, 0, 0, gw.scale, events, self.stream)
+                          self.q.stride(0) * 2, 0, 0, gw.scale,
+                          B.STEP_FUSE_ACROSS_LAYERS if fuse else 0, events, self.stream)
         B.oxy_batch_destroy(batch)
 
 
@@ -136,7 +138,7 @@ def _live_kv_tokens(gw, items):
 def bench_stress(args, device):
     import torch
     from paper_2603_14371_amd import synth
-    w = synth.stress(mixed_steps=args.warmup + 2 * args.steps + 2)
+    w = synth.stress(mixed_steps=args.warmup + 3 * args.steps + 2)
     t0 = time.time()
     gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens)
     setup_s = time.time() - t0
@@ -167,6 +169,13 @@ def bench_stress(args, device):
         runner.step(steps[args.warmup + args.steps + i]["items"], sets[i].raw)
     torch.cuda.synchronize(device)
     step_us_ev = (time.perf_counter() - t_start) / args.steps * 1e6
+    # ---- and once more with the cross-layer launch fusion (merge l + append l+1 in one launch)
+    torch.cuda.synchronize(device)
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        runner.step(steps[args.warmup + 2 * args.steps + i]["items"], fuse=True)
+    torch.cuda.synchronize(device)
+    step_us_fused = (time.perf_counter() - t_start) / args.steps * 1e6
     attn_us = [t for es in sets for t in es.work_us()]
     attn_avg_us = float(np.mean(attn_us))
     merge_avg_us = float(np.mean([t for es in sets for t in es.merge_us()]))
@@ -177,6 +186,7 @@ def bench_stress(args, device):
     res = {
         "step_us": step_us,
         "step_us_with_events": step_us_ev,
+        "step_us_fused": step_us_fused,
         "attn_launch_us": attn_avg_us,
         "merge_launch_us": merge_avg_us,
         "alg_bytes_per_launch": alg_bytes,
@@ -404,6 +414,7 @@ def main():
                      "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
     }
     out["step_us_with_events"] = round(s["step_us_with_events"], 2)
+    out["step_us_merge_append_fused_across_layers"] = round(s["step_us_fused"], 2)
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
     if os.path.exists(traffic_file):
         t = json.load(open(traffic_file))

@@ -173,17 +173,21 @@ int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t laye
                             void *hip_stream);
 /* All layers [layer_begin, layer_end) of one step, in order: for each layer the append and
  * then the mixed attention, with the same kernels and the same effects as the two calls above
- * (this is their loop moved below the ABI: one call per step instead of two per layer, and the
- * merge of layer l shares its launch with the append of layer l+1, which touch disjoint memory).
+ * (this is their loop moved below the ABI: one call per step instead of two per layer).
  * Layer l uses k_new + l*kv_layer_stride, v_new + l*kv_layer_stride (bytes), q + l*q_layer_stride,
  * out + l*q_layer_stride, and lse + l*lse_layer_stride (bytes) when lse is not NULL.
+ * flags: 0 = three launches per layer (append, work items, merge), the order a model imposes
+ * when layer l+1's K/V depend on layer l's output.  OXY_STEP_FUSE_ACROSS_LAYERS = the merge of
+ * layer l shares its launch with the append of layer l+1 (disjoint memory); only meaningful when
+ * every layer's new K/V is known up front (attention-only replay, benchmarking).
  * events: NULL, or HOST array of 3*(layer_end-layer_begin) hipEvent_t recorded on hip_stream per
  * layer: before the work-item kernel, after it, and after the merge (a profiling hook). */
+enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1 };
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,
                         size_t kv_layer_stride, const void *q, void *out, size_t q_layer_stride,
-                        float *lse, size_t lse_layer_stride, float scale, void *const *events,
-                        void *hip_stream);
+                        float *lse, size_t lse_layer_stride, float scale, int32_t flags,
+                        void *const *events, void *hip_stream);
 int32_t oxy_batch_destroy(oxy_batch *batch);
 
 /* Reads K/V rows back in natural order: slots HOST int64 [n] (block*16+offset);

@@ -18,6 +18,7 @@ ERR_BUSY, ERR_WORKSPACE, ERR_DEVICE = -5, -6, -7
 KIND_ACTION, KIND_DECODE = 0, 1
 POOL_HOST_ONLY = 1
 BATCH_APPEND_ONLY = 1
+STEP_FUSE_ACROSS_LAYERS = 1
 
 EXPORTS = [
     "oxy_version", "oxy_last_error", "oxy_kv_bytes", "oxy_workspace_bytes", "oxy_pool_create",
@@ -87,7 +88,7 @@ def lib():
             "oxy_stream_append": [vp, vp, i32, vp, vp, vp],
             "oxy_mixed_attention": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
             "oxy_step_layers": [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp, ctypes.c_size_t,
-                                vp, ctypes.c_size_t, ctypes.c_float, ctypes.POINTER(vp), vp],
+                                vp, ctypes.c_size_t, ctypes.c_float, i32, ctypes.POINTER(vp), vp],
             "oxy_batch_destroy": [vp],
             "oxy_gather_kv": [vp, i32, ctypes.POINTER(ctypes.c_int64), i32, vp, vp, vp],
             "oxy_stream_info": [vp, i32, pi32, pi32, pi32, pi32],
@@ -206,11 +207,11 @@ def oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr, scale, stre
 
 
 def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride, q_ptr,
-                    out_ptr, q_layer_stride, lse_ptr, lse_layer_stride, scale, events, stream):
+                    out_ptr, q_layer_stride, lse_ptr, lse_layer_stride, scale, flags, events, stream):
     """events: None or a ctypes array of 3*(layer_end-layer_begin) raw hipEvent_t handles."""
     _check(lib().oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride,
                                  q_ptr, out_ptr, q_layer_stride, lse_ptr or None, lse_layer_stride,
-                                 ctypes.c_float(scale), events, stream or None))
+                                 ctypes.c_float(scale), flags, events, stream or None))
 
 
 def oxy_batch_destroy(batch):

@@ -738,8 +738,10 @@ int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, cons
 int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, int32_t layer_end,
                         const void* k_new, const void* v_new, size_t kv_layer_stride,
                         const void* q, void* out, size_t q_layer_stride, float* lse,
-                        size_t lse_layer_stride, float scale, void* const* events,
+                        size_t lse_layer_stride, float scale, int32_t flags, void* const* events,
                         void* hip_stream) {
+  if (flags & ~OXY_STEP_FUSE_ACROSS_LAYERS) return fail(OXY_ERR_INVALID_ARG, "step_layers: flags");
+  const bool fuse = (flags & OXY_STEP_FUSE_ACROSS_LAYERS) != 0;
   if (!p || !b || b->pool != p || !k_new || !v_new || !q || !out || p->host_only)
     return fail(OXY_ERR_INVALID_ARG, "step_layers: null argument, foreign batch or host-only pool");
   if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
@@ -757,17 +759,23 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     ap.layer_base = layer_base(p, layer);
     return ap;
   };
-  // Same kernels and the same order of effects as the per-layer calls; the merge of layer l and
-  // the append of layer l+1 (disjoint memory) share one launch.
-  {
-    oxy::AppendArgs first = append_of(layer_begin);
-    hipError_t e = oxy::launch_append(first.k_new, first.v_new, first.d_slots, first.n_tokens,
-                                      first.layer_base, s);
+  // Same kernels and the same order of effects as the per-layer calls.  With `fuse`, the merge
+  // of layer l and the append of layer l+1 (disjoint memory) share one launch.
+  auto append_now = [&](int32_t layer) {
+    oxy::AppendArgs ap = append_of(layer);
+    return oxy::launch_append(ap.k_new, ap.v_new, ap.d_slots, ap.n_tokens, ap.layer_base, s);
+  };
+  if (fuse) {
+    hipError_t e = append_now(layer_begin);
     if (e != hipSuccess) return hip_fail(e, "step_layers: append");
   }
   for (int32_t layer = layer_begin; layer < layer_end; ++layer) {
     const size_t i = (size_t)(layer - layer_begin);
     hipError_t e = hipSuccess;
+    if (!fuse) {
+      e = append_now(layer);
+      if (e != hipSuccess) return hip_fail(e, "step_layers: append");
+    }
     if (events) e = hipEventRecord((hipEvent_t)events[3 * i], s);
     if (e != hipSuccess) return hip_fail(e, "step_layers: event");
     oxy::AttnArgs a = attn_args(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
@@ -778,7 +786,7 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     if (e != hipSuccess) return hip_fail(e, "step_layers: attention");
     if (events) e = hipEventRecord((hipEvent_t)events[3 * i + 1], s);
     if (e != hipSuccess) return hip_fail(e, "step_layers: event");
-    if (layer + 1 < layer_end) {
+    if (fuse && layer + 1 < layer_end) {
       oxy::AppendArgs nx = append_of(layer + 1);
       e = oxy::launch_merge_append(a, &nx, s);
     } else {

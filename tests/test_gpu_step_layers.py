@@ -16,7 +16,7 @@ def test_step_layers_equals_per_layer_calls():
     w = synth.tiny(prefix_len=200, chunk=50, prior=77, n_layers=5)
     data = synth.DataSource(31337)
     results = {}
-    for mode in ("per_layer", "step_layers"):
+    for mode in ("per_layer", "step_layers", "step_layers_fused"):
         gw = GpuWorld(w, data, split_tokens=64)
         gw.run(w["trace"][:-1])                     # everything but the final mixed step
         op = w["trace"][-1]
@@ -37,7 +37,8 @@ def test_step_layers_equals_per_layer_calls():
         else:
             B.oxy_step_layers(gw.pool, batch, 0, L, k.data_ptr(), v.data_ptr(), k.stride(0) * 2,
                               q.data_ptr(), o.data_ptr(), q.stride(0) * 2, lse.data_ptr(),
-                              lse.stride(0) * 4, gw.scale, None, stream)
+                              lse.stride(0) * 4, gw.scale,
+                              B.STEP_FUSE_ACROSS_LAYERS if mode.endswith("fused") else 0, None, stream)
         torch.cuda.synchronize()
         B.oxy_batch_destroy(batch)
         pools = []
@@ -46,9 +47,11 @@ def test_step_layers_equals_per_layer_calls():
             pools.append([gw.gather(l, slots) for l in range(L)])
         results[mode] = (bits_of(o), lse.cpu().numpy(), pools)
         gw.close()
-    a, b = results["per_layer"], results["step_layers"]
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
-    assert np.all(np.isfinite(b[1])) and np.any(b[0] != 0)
-    for pa, pb in zip(a[2], b[2]):
-        for (ka, va), (kb, vb) in zip(pa, pb):
-            assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    a = results["per_layer"]
+    for other in ("step_layers", "step_layers_fused"):
+        b = results[other]
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), other
+        assert np.all(np.isfinite(b[1])) and np.any(b[0] != 0)
+        for pa, pb in zip(a[2], b[2]):
+            for (ka, va), (kb, vb) in zip(pa, pb):
+                assert np.array_equal(ka, kb) and np.array_equal(va, vb), other
