@@ -101,24 +101,24 @@ class StepRunner:
 
 
 class EventSet:
-    """3*L timing events per step (before the work-item kernel, after it, after the merge),
-    handed to the library as raw handles."""
+    """4*L timing events per step, handed to the library as raw handles: per layer the begin and
+    end of the work-item kernel and of the merge kernel (the kernels' own timestamps)."""
 
     def __init__(self, n_layers):
         import ctypes
         import torch
-        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n_layers)]
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(4 * n_layers)]
         for e in self.ev:
             e.record()          # creates the underlying hipEvent_t
         self.raw = (ctypes.c_void_p * len(self.ev))(*[e.cuda_event for e in self.ev])
 
     def work_us(self):
-        return [self.ev[3 * i].elapsed_time(self.ev[3 * i + 1]) * 1e3
-                for i in range(len(self.ev) // 3)]
+        return [self.ev[4 * i].elapsed_time(self.ev[4 * i + 1]) * 1e3
+                for i in range(len(self.ev) // 4)]
 
     def merge_us(self):
-        return [self.ev[3 * i + 1].elapsed_time(self.ev[3 * i + 2]) * 1e3
-                for i in range(len(self.ev) // 3)]
+        return [self.ev[4 * i + 2].elapsed_time(self.ev[4 * i + 3]) * 1e3
+                for i in range(len(self.ev) // 4)]
 
 
 def _live_kv_tokens(gw, items):

@@ -180,8 +180,9 @@ int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t laye
  * when layer l+1's K/V depend on layer l's output.  OXY_STEP_FUSE_ACROSS_LAYERS = the merge of
  * layer l shares its launch with the append of layer l+1 (disjoint memory); only meaningful when
  * every layer's new K/V is known up front (attention-only replay, benchmarking).
- * events: NULL, or HOST array of 3*(layer_end-layer_begin) hipEvent_t recorded on hip_stream per
- * layer: before the work-item kernel, after it, and after the merge (a profiling hook). */
+ * events: NULL, or HOST array of 4*(layer_end-layer_begin) created hipEvent_t; per layer they
+ * receive the begin and end timestamps of the work-item kernel and of the merge kernel
+ * themselves (hipExtLaunchKernel start/stop events; a profiling hook). */
 enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1 };
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,

@@ -208,7 +208,7 @@ def oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr, scale, stre
 
 def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride, q_ptr,
                     out_ptr, q_layer_stride, lse_ptr, lse_layer_stride, scale, flags, events, stream):
-    """events: None or a ctypes array of 3*(layer_end-layer_begin) raw hipEvent_t handles."""
+    """events: None or a ctypes array of 4*(layer_end-layer_begin) raw hipEvent_t handles."""
     _check(lib().oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride,
                                  q_ptr, out_ptr, q_layer_stride, lse_ptr or None, lse_layer_stride,
                                  ctypes.c_float(scale), flags, events, stream or None))

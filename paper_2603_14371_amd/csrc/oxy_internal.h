@@ -55,7 +55,9 @@ struct AttnArgs {
   float scale;
 };
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);       // work items, then merge
-hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s);  // work items only
+// work items only; start/stop (may be null) receive the kernel's own begin/end timestamps
+hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s, hipEvent_t start = nullptr,
+                                 hipEvent_t stop = nullptr);
 struct AppendArgs {
   const void* k_new;
   const void* v_new;
@@ -64,7 +66,8 @@ struct AppendArgs {
   void* layer_base;
 };
 // merge of `a`, and in the same launch the append described by `next` (may be null)
-hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s);
+hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s,
+                               hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 }  // namespace oxy

@@ -27,6 +27,8 @@
 // want (see oxy.h): every MFMA operand is one aligned 16-byte load.
 #include "oxy_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace oxy {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -656,18 +658,32 @@ __global__ __launch_bounds__(256) void merge_append_kernel(const AttnArgs a, con
   }
 }
 
-hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s) {
+hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s, hipEvent_t start,
+                                 hipEvent_t stop) {
   if (a.n_work <= 0 || a.n_q <= 0) return hipErrorInvalidValue;
-  attn_kernel<<<a.n_work, 256, 0, s>>>(a);
+  if (start || stop)
+    hipExtLaunchKernelGGL(attn_kernel, dim3(a.n_work), dim3(256), 0, s, start, stop, 0, a);
+  else
+    attn_kernel<<<a.n_work, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
-hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s) {
+hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s,
+                               hipEvent_t start, hipEvent_t stop) {
   if (a.n_q <= 0) return hipErrorInvalidValue;
-  if (next && next->n_tokens > 0)
-    merge_append_kernel<<<2 * a.n_q + next->n_tokens, 256, 0, s>>>(a, *next);
-  else
-    merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
+  const bool timed = start || stop;
+  if (next && next->n_tokens > 0) {
+    const dim3 grid(2 * a.n_q + next->n_tokens);
+    if (timed)
+      hipExtLaunchKernelGGL(merge_append_kernel, grid, dim3(256), 0, s, start, stop, 0, a, *next);
+    else
+      merge_append_kernel<<<grid, 256, 0, s>>>(a, *next);
+  } else {
+    if (timed)
+      hipExtLaunchKernelGGL(merge_kernel, dim3(2 * a.n_q), dim3(256), 0, s, start, stop, 0, a);
+    else
+      merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
+  }
   return hipGetLastError();
 }
 

@@ -776,25 +776,22 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
       e = append_now(layer);
       if (e != hipSuccess) return hip_fail(e, "step_layers: append");
     }
-    if (events) e = hipEventRecord((hipEvent_t)events[3 * i], s);
-    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    if (events)
+      for (int j = 0; j < 4; ++j) ev[j] = (hipEvent_t)events[4 * i + j];
     oxy::AttnArgs a = attn_args(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
                                 (char*)out + (size_t)layer * q_layer_stride,
                                 lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
                                 scale);
-    e = oxy::launch_attention_work(a, s);
+    e = oxy::launch_attention_work(a, s, ev[0], ev[1]);
     if (e != hipSuccess) return hip_fail(e, "step_layers: attention");
-    if (events) e = hipEventRecord((hipEvent_t)events[3 * i + 1], s);
-    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
     if (fuse && layer + 1 < layer_end) {
       oxy::AppendArgs nx = append_of(layer + 1);
-      e = oxy::launch_merge_append(a, &nx, s);
+      e = oxy::launch_merge_append(a, &nx, s, ev[2], ev[3]);
     } else {
-      e = oxy::launch_merge_append(a, nullptr, s);
+      e = oxy::launch_merge_append(a, nullptr, s, ev[2], ev[3]);
     }
     if (e != hipSuccess) return hip_fail(e, "step_layers: merge");
-    if (events) e = hipEventRecord((hipEvent_t)events[3 * i + 2], s);
-    if (e != hipSuccess) return hip_fail(e, "step_layers: event");
   }
   return OXY_OK;
 }
