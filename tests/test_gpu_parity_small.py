@@ -58,3 +58,12 @@ def test_multi_token_decode_queries_are_causal():
     w = _workload("multi_token", 99, 2, 64, b.trace)
     gw, g, ow, o = run_both(w, split_tokens=32)
     _finish(gw, ow)
+
+
+@pytest.mark.parametrize("tile,stream", [(512, 512), (1024, 1024), (32, 32), (96, 160)])
+def test_split_sizes_including_block_table_fallback(tile, stream):
+    """Splits longer than 16 pages take their block ids from the block table instead of the
+    work record's inline copy; the shortest and odd sizes exercise ragged last splits."""
+    w = synth.tiny(prefix_len=1100, chunk=37, prior=700, n_layers=2)
+    gw, g, ow, o = run_both(w, split_tokens=tile, stream_split_tokens=stream, max_partials=4096)
+    _finish(gw, ow)
