@@ -97,14 +97,50 @@ __global__ __launch_bounds__(256) void append_kernel(const uint16_t* __restrict_
              threadIdx.x);
 }
 
-__global__ __launch_bounds__(256) void append_inline_kernel(const uint16_t* __restrict__ k_new,
+// Append of a run of consecutive positions of one table (a prefix): one workgroup per block.
+// A block that is covered completely is written as whole 16-byte chunks (V transposed through
+// LDS); a partly covered block falls back to the per-row scatter so that nothing else in the
+// page is touched.
+__global__ __launch_bounds__(256) void append_blocks_kernel(const uint16_t* __restrict__ k_new,
                                                             const uint16_t* __restrict__ v_new,
                                                             const InlineIds blocks, int32_t pos0,
+                                                            int32_t n_tokens,
                                                             char* __restrict__ layer_base) {
-  const int tok = blockIdx.x;
-  const int pos = pos0 + tok;
-  append_row(k_new + (size_t)tok * kDim, v_new + (size_t)tok * kDim,
-             blocks.v[pos >> 4] * kPage + (pos & 15), layer_base, threadIdx.x);
+  __shared__ __align__(16) uint16_t v_s[kPage][kDim + 8];   // +8: rows land in different banks
+  const int t = threadIdx.x;
+  const int first_page = pos0 >> 4;
+  const int page = first_page + blockIdx.x;
+  const int lo = max(pos0, page * kPage), hi = min(pos0 + n_tokens, (page + 1) * kPage);
+  const int blk = blocks.v[blockIdx.x];
+  if (hi - lo < kPage) {
+    for (int pos = lo; pos < hi; ++pos)
+      append_row(k_new + (size_t)(pos - pos0) * kDim, v_new + (size_t)(pos - pos0) * kDim,
+                 blk * kPage + (pos & 15), layer_base, t);
+    return;
+  }
+  char* kp = layer_base + (size_t)blk * kBlockBytes;
+  char* vp = kp + kPageBytes;
+  const uint16_t* k_src = k_new + (size_t)(lo - pos0) * kDim;
+  const uint16_t* v_src = v_new + (size_t)(lo - pos0) * kDim;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = t + 256 * i, key = idx >> 5, cd = idx & 31;
+    *(u32x4*)(kp + k_chunk_offset(cd >> 2, key >> 3, cd & 3, key & 7)) =
+        *(const u32x4*)(k_src + (size_t)key * kDim + cd * 8);
+    *(u32x4*)(&v_s[key][cd * 8]) = *(const u32x4*)(v_src + (size_t)key * kDim + cd * 8);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int ci = t + 256 * i, c = ci >> 5, gp = (ci >> 4) & 1, m = ci & 15, d = 16 * c + m;
+    u32x4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int k0 = (e < 2 ? 4 * gp : 8 + 4 * gp) + 2 * (e & 1);
+      out[e] = (uint32_t)v_s[k0][d] | ((uint32_t)v_s[k0 + 1][d] << 16);
+    }
+    *(u32x4*)(vp + v_chunk_offset(c, gp, m)) = out;
+  }
 }
 
 __global__ __launch_bounds__(256) void gather_inline_kernel(const char* __restrict__ layer_base,
@@ -134,8 +170,10 @@ hipError_t launch_append(const void* k_new, const void* v_new, const int32_t* d_
 hipError_t launch_append_inline(const void* k_new, const void* v_new, const InlineIds& blocks,
                                 int32_t pos0, int32_t n_tokens, void* layer_base, hipStream_t s) {
   if (n_tokens <= 0) return hipSuccess;
-  append_inline_kernel<<<n_tokens, 256, 0, s>>>((const uint16_t*)k_new, (const uint16_t*)v_new,
-                                                blocks, pos0, (char*)layer_base);
+  // blocks.v[i] is the block of page (pos0 / 16 + i)
+  const int32_t n_pages = ((pos0 + n_tokens + kPage - 1) >> 4) - (pos0 >> 4);
+  append_blocks_kernel<<<n_pages, 256, 0, s>>>((const uint16_t*)k_new, (const uint16_t*)v_new,
+                                               blocks, pos0, n_tokens, (char*)layer_base);
   return hipGetLastError();
 }
 

@@ -13,7 +13,6 @@
 #include <cstring>
 #include <new>
 #include <unordered_map>
-#include <unordered_set>
 #include <vector>
 
 namespace {
@@ -47,6 +46,7 @@ struct Stream {
   int32_t kind = 0;
   std::vector<int32_t> blocks;
   int32_t len = 0;
+  uint64_t stamp = 0;  // last batch build that listed this stream
 };
 
 // One descriptor slot in the caller's workspace plus its staging buffer.
@@ -74,6 +74,7 @@ struct oxy_pool {
   size_t acc_offset = 0, ml_offset = 0;
   std::vector<DescSlot> slots;
   int32_t live_batches = 0;
+  uint64_t build_seq = 0;
 };
 
 struct oxy_batch {
@@ -391,26 +392,27 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   // ---- validate everything before touching state
   struct Plan {
     Stream* s;
-    int32_t sid, old_len, new_len, need, tok0;
+    int32_t old_len, new_len, need, tok0;
   };
   std::vector<Plan> plan;
   plan.reserve(n_items);
-  std::unordered_set<int32_t> seen;
+  const uint64_t stamp = ++p->build_seq;   // marks the streams of this build (duplicate check)
   int64_t need_total = 0, n_tokens = 0;
   for (int32_t i = 0; i < n_items; ++i) {
     auto it = p->streams.find(items[i].stream_id);
     if (it == p->streams.end())
       return fail(OXY_ERR_BAD_ID, "batch_build: no stream %d", items[i].stream_id);
-    if (items[i].n_new < 1 || !seen.insert(items[i].stream_id).second)
+    Stream& s = it->second;
+    if (items[i].n_new < 1 || s.stamp == stamp)
       return fail(OXY_ERR_INVALID_ARG, "batch_build: item %d: n_new %d or duplicate stream", i,
                   items[i].n_new);
-    Stream& s = it->second;
+    s.stamp = stamp;
     int32_t old_len = s.kind == OXY_KIND_ACTION ? 0 : s.len;
     int64_t new_len = (int64_t)old_len + items[i].n_new;
     if (new_len > (int64_t)kPage * c.num_blocks)
       return fail(OXY_ERR_NO_BLOCKS, "batch_build: stream %d would exceed the pool", items[i].stream_id);
     int32_t need = std::max(0, blocks_for((int32_t)new_len) - (int32_t)s.blocks.size());
-    plan.push_back({&s, items[i].stream_id, old_len, (int32_t)new_len, need, (int32_t)n_tokens});
+    plan.push_back({&s, old_len, (int32_t)new_len, need, (int32_t)n_tokens});
     need_total += need;
     n_tokens += items[i].n_new;
   }
@@ -424,21 +426,26 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     return fail(OXY_ERR_WORKSPACE, "batch_build: %lld query tokens > max_q_tokens %d",
                 (long long)n_tokens, c.max_q_tokens);
 
-  // ---- work list on the lengths the step will have (state still untouched)
-  std::vector<int32_t> work, toks, tables, n_parts(append_only ? 0 : n_tokens, 0);
-  std::vector<int32_t> tbl_lens;  // (offset, count) pairs to fill after allocation
+  // ---- work list on the lengths the step will have (state still untouched).  Records are
+  // kept as their eight header words until the order is known.
+  constexpr int kHdr = 8;
+  std::vector<int32_t> hdr, toks, n_parts(append_only ? 0 : n_tokens, 0);
   struct TableRef {
     int32_t off;
     const std::vector<int32_t>* src;
     int32_t count;
   };
   std::vector<TableRef> table_refs;
+  std::vector<int32_t> order;   // final order of the records; -1 = padding record
   int32_t tbl_words = 0;
   if (!append_only) {
+    hdr.reserve(1024 * kHdr);
+    toks.reserve(2 * n_tokens);
+    table_refs.reserve(n_items + 8);
     auto add_work = [&](int32_t tok_off, int32_t n_tok, int32_t tbl_off, int32_t b, int32_t e,
                         int32_t q0, int32_t part, int32_t path) {
-      int32_t w[oxy::kWorkWords] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
-      work.insert(work.end(), w, w + oxy::kWorkWords);   // words 8.. are filled after commit
+      const int32_t w[kHdr] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
+      hdr.insert(hdr.end(), w, w + kHdr);
     };
     // Which path evaluates a query depends on its item only (kind, n_new, phase), never on its
     // batch mates, so an item's arithmetic is the same in every batch it can appear in:
@@ -446,132 +453,142 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     //   own phase    -> items with <= 2 new tokens (decode) stream their own pages;
     //                   larger items (action chunks, multi-token decode) use tiles of 8.
     const int32_t tile_tok = 8;
-    std::vector<int32_t> group_order;
-    std::unordered_map<int32_t, std::vector<int32_t>> group_toks;
+    struct Group {
+      int32_t pid;
+      const Prefix* px;
+      std::vector<int32_t> toks;
+    };
+    std::vector<Group> groups;   // in order of first appearance; a batch touches few prefixes
+    groups.reserve(16);
     for (const Plan& pl : plan) {
-      int32_t pid = pl.s->prefix_id;
+      const int32_t pid = pl.s->prefix_id;
       if (pid == -1) continue;
-      if (p->prefixes.at(pid).len == 0) continue;
-      auto ins = group_toks.emplace(pid, std::vector<int32_t>());
-      if (ins.second) group_order.push_back(pid);
-      for (int32_t t = 0; t < pl.new_len - pl.old_len; ++t) ins.first->second.push_back(pl.tok0 + t);
+      Group* g = nullptr;
+      for (Group& x : groups)
+        if (x.pid == pid) {
+          g = &x;
+          break;
+        }
+      if (!g) {
+        const Prefix& px = p->prefixes.at(pid);
+        if (px.len == 0) continue;
+        groups.push_back({pid, &px, {}});
+        g = &groups.back();
+      }
+      for (int32_t t = 0; t < pl.new_len - pl.old_len; ++t) g->toks.push_back(pl.tok0 + t);
     }
-    for (int32_t pid : group_order) {
-      const Prefix& px = p->prefixes.at(pid);
-      const std::vector<int32_t>& gt = group_toks[pid];
-      int32_t tbl_off = tbl_words;
+    for (const Group& g : groups) {
+      const Prefix& px = *g.px;
+      const int32_t tbl_off = tbl_words;
       table_refs.push_back({tbl_off, &px.blocks, blocks_for(px.len)});
       tbl_words += blocks_for(px.len);
       const int32_t split = tile_split_for(c, px.len);
-      int32_t nsplit = (px.len + split - 1) / split;
-      for (size_t t0 = 0; t0 < gt.size(); t0 += tile_tok) {
-        int32_t n = (int32_t)std::min<size_t>(tile_tok, gt.size() - t0);
-        int32_t tok_off = (int32_t)toks.size();
-        toks.insert(toks.end(), gt.begin() + t0, gt.begin() + t0 + n);
+      const int32_t nsplit = (px.len + split - 1) / split;
+      for (size_t t0 = 0; t0 < g.toks.size(); t0 += tile_tok) {
+        const int32_t n = (int32_t)std::min<size_t>(tile_tok, g.toks.size() - t0);
+        const int32_t tok_off = (int32_t)toks.size();
+        toks.insert(toks.end(), g.toks.begin() + t0, g.toks.begin() + t0 + n);
         for (int32_t s = 0; s < nsplit; ++s)
           add_work(tok_off, n, tbl_off, s * split, std::min(px.len, (s + 1) * split),
                    oxy::kNoCausal, s, oxy::PATH_TILE);
       }
-      for (int32_t t : gt) n_parts[t] = nsplit;
+      for (int32_t t : g.toks) n_parts[t] = nsplit;
     }
     for (const Plan& pl : plan) {
-      int32_t tbl_off = tbl_words;
+      const int32_t tbl_off = tbl_words;
       table_refs.push_back({tbl_off, &pl.s->blocks, blocks_for(pl.new_len)});
       tbl_words += blocks_for(pl.new_len);
-      int32_t n_new = pl.new_len - pl.old_len;
-      bool causal = pl.s->kind == OXY_KIND_DECODE;
+      const int32_t n_new = pl.new_len - pl.old_len;
+      const bool causal = pl.s->kind == OXY_KIND_DECODE;
       const int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
-      const int32_t split = n_new <= 2 ? c.stream_split_tokens
-                                       : tile_split_for(c, pl.new_len);
+      const int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
-        int32_t n = std::min(step_tok, n_new - t0);
-        int32_t tok_off = (int32_t)toks.size();
+        const int32_t n = std::min(step_tok, n_new - t0);
+        const int32_t tok_off = (int32_t)toks.size();
         for (int32_t t = 0; t < n; ++t) toks.push_back(pl.tok0 + t0 + t);
-        int32_t q0 = pl.old_len + t0;
-        int32_t kv_hi = causal ? q0 + n : pl.new_len;
-        int32_t nsplit = (kv_hi + split - 1) / split;
-        int32_t base = n_parts[pl.tok0 + t0];
+        const int32_t q0 = pl.old_len + t0;
+        const int32_t kv_hi = causal ? q0 + n : pl.new_len;
+        const int32_t nsplit = (kv_hi + split - 1) / split;
+        const int32_t base = n_parts[pl.tok0 + t0];
         for (int32_t s = 0; s < nsplit; ++s)
           add_work(tok_off, n, tbl_off, s * split, std::min(kv_hi, (s + 1) * split),
                    causal ? q0 : oxy::kNoCausal, base + s, path);
         for (int32_t t = 0; t < n; ++t) n_parts[pl.tok0 + t0 + t] += nsplit;
       }
     }
-#ifdef OXY_DEBUG_PROBES
-    if (const char* dbg = getenv("OXY_DEBUG_ONLY_PATH")) {  // timing probe, never built by default
-      int keep = atoi(dbg);
-      std::vector<int32_t> kept;
-      for (size_t i = 0; i < work.size(); i += oxy::kWorkWords)
-        if (work[i + oxy::W_PATH] == keep) kept.insert(kept.end(), &work[i], &work[i] + oxy::kWorkWords);
-      work.swap(kept);
-    }
-#endif
     // Order of the work list.  Workgroup i runs on XCD i % 8 and every XCD has its own L2, so
     // tiles that read the same pages (same table, same split) are given indices of one residue
-    // class; within a class the longest work comes first, and the classes are balanced by cost.
+    // class; within a class the longest work comes first, and the classes are balanced by cost
+    // (longest-processing-time rule over the groups).  Padding records keep the pattern intact.
     {
-      const int32_t nw = (int32_t)(work.size() / oxy::kWorkWords);
+      const int32_t nw = (int32_t)(hdr.size() / kHdr);
       constexpr int kXcd = 8;
-      auto rec = [&](int32_t i) { return &work[(size_t)i * oxy::kWorkWords]; };
-      auto cost = [&](int32_t i) {
-        const int32_t* r = rec(i);
-        int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
-        return r[oxy::W_PATH] == oxy::PATH_TILE ? 2 * steps : steps;
+      struct Rec {
+        int64_t key;     // tiles: (table, split begin); streaming items: unique
+        int32_t idx, cost;
       };
-      std::vector<std::vector<int32_t>> groups;
-      std::unordered_map<int64_t, int32_t> group_of;
+      std::vector<Rec> recs(nw);
       for (int32_t i = 0; i < nw; ++i) {
-        const int32_t* r = rec(i);
-        if (r[oxy::W_PATH] == oxy::PATH_TILE) {
-          int64_t key = ((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN];
-          auto ins = group_of.emplace(key, (int32_t)groups.size());
-          if (ins.second) groups.emplace_back();
-          groups[ins.first->second].push_back(i);
-        } else {
-          groups.push_back({i});
-        }
+        const int32_t* r = &hdr[(size_t)i * kHdr];
+        const int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
+        const bool tile = r[oxy::W_PATH] == oxy::PATH_TILE;
+        recs[i].idx = i;
+        recs[i].cost = tile ? 2 * steps : steps;
+        recs[i].key = tile ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
+                           : -(int64_t)i - 1;
       }
-      std::vector<int64_t> gcost(groups.size(), 0);
-      for (size_t gi = 0; gi < groups.size(); ++gi)
-        for (int32_t i : groups[gi]) gcost[gi] += cost(i);
-      std::vector<int32_t> gorder(groups.size());
-      for (size_t gi = 0; gi < groups.size(); ++gi) gorder[gi] = (int32_t)gi;
-      std::stable_sort(gorder.begin(), gorder.end(),
-                       [&](int32_t x, int32_t y) { return gcost[x] > gcost[y]; });
-      std::vector<int32_t> queue[kXcd];
+      std::stable_sort(recs.begin(), recs.end(),
+                       [](const Rec& a, const Rec& b) { return a.key < b.key; });
+      struct Grp {
+        int32_t first, count;
+        int64_t cost;
+      };
+      std::vector<Grp> grps;
+      grps.reserve(nw);
+      for (int32_t i = 0; i < nw;) {
+        int32_t j = i;
+        int64_t cst = 0;
+        while (j < nw && recs[j].key == recs[i].key) cst += recs[j++].cost;
+        grps.push_back({i, j - i, cst});
+        i = j;
+      }
+      std::stable_sort(grps.begin(), grps.end(), [&](const Grp& a, const Grp& b) {
+        return a.cost != b.cost ? a.cost > b.cost : recs[a.first].idx < recs[b.first].idx;
+      });
+      std::vector<Rec> queue[kXcd];
       int64_t qcost[kXcd] = {0};
-      for (int32_t gi : gorder) {
+      for (int x = 0; x < kXcd; ++x) queue[x].reserve(nw / kXcd + 16);
+      for (const Grp& g : grps) {
         int best = 0;
         for (int x = 1; x < kXcd; ++x)
           if (qcost[x] < qcost[best]) best = x;
-        queue[best].insert(queue[best].end(), groups[gi].begin(), groups[gi].end());
-        qcost[best] += gcost[gi];
+        queue[best].insert(queue[best].end(), recs.begin() + g.first,
+                           recs.begin() + g.first + g.count);
+        qcost[best] += g.cost;
       }
       size_t longest = 0;
       for (int x = 0; x < kXcd; ++x) {
-        std::stable_sort(queue[x].begin(), queue[x].end(),
-                         [&](int32_t a2, int32_t b2) { return cost(a2) > cost(b2); });
+        std::stable_sort(queue[x].begin(), queue[x].end(), [](const Rec& a, const Rec& b) {
+          return a.cost != b.cost ? a.cost > b.cost : a.idx < b.idx;
+        });
         longest = std::max(longest, queue[x].size());
       }
-      std::vector<int32_t> sorted;
-      sorted.reserve(longest * kXcd * oxy::kWorkWords);
-      int32_t noop[oxy::kWorkWords] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
+      order.reserve(longest * kXcd);
       size_t last_real = 0;
       for (size_t k = 0; k < longest; ++k)
         for (int x = 0; x < kXcd; ++x) {
           if (k < queue[x].size()) {
-            sorted.insert(sorted.end(), rec(queue[x][k]), rec(queue[x][k]) + oxy::kWorkWords);
-            last_real = sorted.size();
+            order.push_back(queue[x][k].idx);
+            last_real = order.size();
           } else {
-            sorted.insert(sorted.end(), noop, noop + oxy::kWorkWords);
+            order.push_back(-1);
           }
         }
-      sorted.resize(last_real);
-      work.swap(sorted);
+      order.resize(last_real);
     }
   }
-  int32_t n_work = (int32_t)(work.size() / oxy::kWorkWords);
+  const int32_t n_work = (int32_t)order.size();
   int64_t n_partials = 0;
   std::vector<int32_t> part_off(n_parts.size());
   for (size_t t = 0; t < n_parts.size(); ++t) {
@@ -584,8 +601,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   if (n_partials > c.max_partials)
     return fail(OXY_ERR_WORKSPACE, "batch_build: %lld partials > max_partials %d",
                 (long long)n_partials, c.max_partials);
-  if ((size_t)tbl_words > (size_t)c.num_blocks + (size_t)need_total)
-    return fail(OXY_ERR_WORKSPACE, "batch_build: block tables too long");
+  if (tbl_words > c.num_blocks) return fail(OXY_ERR_WORKSPACE, "batch_build: block tables too long");
 
   // ---- a free descriptor slot
   int32_t slot = -1;
@@ -599,39 +615,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   oxy_batch* b = new (std::nothrow) oxy_batch();
   if (!b) return fail(OXY_ERR_INVALID_ARG, "batch_build: out of host memory");
 
-  // ---- commit: take blocks in item order, record slots
-  std::vector<int32_t> slots_v;
-  slots_v.reserve(n_tokens);
-  for (Plan& pl : plan) {
-    for (int32_t i = 0; i < pl.need; ++i) {
-      int32_t blk = p->free_stack.back();
-      p->free_stack.pop_back();
-      p->ref[blk] = 1;
-      pl.s->blocks.push_back(blk);
-    }
-    pl.s->len = pl.new_len;
-    for (int32_t t = pl.old_len; t < pl.new_len; ++t)
-      slots_v.push_back(pl.s->blocks[t / kPage] * kPage + t % kPage);
-  }
-  for (const TableRef& tr : table_refs) {
-    if ((int32_t)tables.size() < tr.off + tr.count) tables.resize(tr.off + tr.count);
-    std::copy(tr.src->begin(), tr.src->begin() + tr.count, tables.begin() + tr.off);
-  }
-
-  // ---- inline copies in every work record: its token ids and the block ids of its first pages,
-  // so a workgroup needs one 128-byte load before it can issue its first pages
-  for (size_t r = 0; r + oxy::kWorkWords <= work.size(); r += oxy::kWorkWords) {
-    int32_t* w = &work[r];
-    if (w[oxy::W_PATH] == oxy::PATH_NOOP) continue;
-    for (int32_t i = 0; i < oxy::kWorkInlineToks; ++i)
-      w[8 + i] = toks[w[oxy::W_TOK_OFF] + std::min(i, w[oxy::W_N_TOK] - 1)];
-    const int32_t pg0 = w[oxy::W_KV_BEGIN] / kPage;
-    const int32_t npg = blocks_for(w[oxy::W_KV_END]) - pg0;
-    for (int32_t i = 0; i < oxy::kWorkInlinePages; ++i)
-      w[16 + i] = tables[w[oxy::W_TBL_OFF] + pg0 + std::min(i, npg - 1)];
-  }
-
-  // ---- descriptor image
+  // ---- commit: take blocks in item order; the descriptor image is filled in place
   b->pool = p;
   b->slot = slot;
   b->flags = flags;
@@ -639,23 +623,58 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   b->n_tokens = (int32_t)n_tokens;
   b->n_work = n_work;
   b->n_partials = (int32_t)n_partials;
+  b->off_slots = 0;
+  b->off_work = b->off_slots + (int32_t)n_tokens;
+  b->off_toks = b->off_work + n_work * oxy::kWorkWords;
+  b->off_tables = b->off_toks + (int32_t)toks.size();
+  b->off_part_off = b->off_tables + tbl_words;
+  b->off_n_parts = b->off_part_off + (int32_t)part_off.size();
   std::vector<int32_t>& h = b->host;
-  auto put = [&](const std::vector<int32_t>& v) {
-    int32_t off = (int32_t)h.size();
-    h.insert(h.end(), v.begin(), v.end());
-    return off;
-  };
-  b->off_slots = put(slots_v);
-  b->off_work = put(work);
-  b->off_toks = put(toks);
-  b->off_tables = put(tables);
-  b->off_part_off = put(part_off);
-  b->off_n_parts = put(n_parts);
-  if (h.size() > p->desc_words) {
+  h.resize((size_t)b->off_n_parts + n_parts.size());
+  if (h.size() > p->desc_words) {   // cannot happen: every section was bounded above
     delete b;
-    // state was committed; this cannot happen because every section was bounded above
     return fail(OXY_ERR_WORKSPACE, "batch_build: descriptor overflow (internal)");
   }
+  {
+    int32_t* sl = &h[b->off_slots];
+    for (Plan& pl : plan) {
+      for (int32_t i = 0; i < pl.need; ++i) {
+        int32_t blk = p->free_stack.back();
+        p->free_stack.pop_back();
+        p->ref[blk] = 1;
+        pl.s->blocks.push_back(blk);
+      }
+      pl.s->len = pl.new_len;
+      for (int32_t t = pl.old_len; t < pl.new_len; ++t)
+        *sl++ = pl.s->blocks[t / kPage] * kPage + t % kPage;
+    }
+  }
+  int32_t* tables = h.data() + b->off_tables;
+  for (const TableRef& tr : table_refs)
+    std::copy(tr.src->begin(), tr.src->begin() + tr.count, tables + tr.off);
+  std::copy(toks.begin(), toks.end(), h.begin() + b->off_toks);
+  std::copy(part_off.begin(), part_off.end(), h.begin() + b->off_part_off);
+  std::copy(n_parts.begin(), n_parts.end(), h.begin() + b->off_n_parts);
+  // Work records, 128 bytes each: header, then inline copies of the tile's token ids and of the
+  // block ids of the split's first pages, so a workgroup needs one load before its first pages.
+  for (int32_t i = 0; i < n_work; ++i) {
+    int32_t* w = &h[(size_t)b->off_work + (size_t)i * oxy::kWorkWords];
+    if (order[i] < 0) {
+      const int32_t noop[kHdr] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
+      std::copy(noop, noop + kHdr, w);
+      std::fill(w + kHdr, w + oxy::kWorkWords, 0);
+      continue;
+    }
+    const int32_t* r = &hdr[(size_t)order[i] * kHdr];
+    std::copy(r, r + kHdr, w);
+    for (int32_t k = 0; k < oxy::kWorkInlineToks; ++k)
+      w[8 + k] = toks[r[oxy::W_TOK_OFF] + std::min(k, r[oxy::W_N_TOK] - 1)];
+    const int32_t pg0 = r[oxy::W_KV_BEGIN] / kPage;
+    const int32_t npg = blocks_for(r[oxy::W_KV_END]) - pg0;
+    for (int32_t k = 0; k < oxy::kWorkInlinePages; ++k)
+      w[16 + k] = tables[r[oxy::W_TBL_OFF] + pg0 + std::min(k, npg - 1)];
+  }
+
   DescSlot& ds = p->slots[slot];
   if (!p->host_only) {
     if (ds.event_pending) {
