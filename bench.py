@@ -317,6 +317,35 @@ def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
     return out
 
 
+def stream_probe(device, n_bytes, layers=18, reps=5):
+    """What a plain read-only streaming kernel reaches on this machine for the same bytes per
+    launch as one attention launch (cycling over `layers` distinct regions so that nothing sits
+    in the memory-side cache), and for a launch four times as large."""
+    import torch
+    from paper_2603_14371_amd import binding as B
+    out = {}
+    stream = torch.cuda.current_stream(device).cuda_stream
+    sink = torch.zeros(64, dtype=torch.uint8, device=device)
+    for label, nb in (("same_bytes", n_bytes), ("4x_bytes", 4 * n_bytes)):
+        nb = (int(nb) // (128 * 1024)) * (128 * 1024)
+        buf = torch.empty(layers * nb, dtype=torch.uint8, device=device).fill_(3)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(reps * layers)]
+        torch.cuda.synchronize(device)
+        for r in range(reps):
+            for l in range(layers):
+                a, b = ev[r * layers + l]
+                a.record()
+                B.oxy_read_probe(buf.data_ptr() + l * nb, nb, sink.data_ptr(), stream)
+                b.record()
+        torch.cuda.synchronize(device)
+        us = [a.elapsed_time(b) * 1e3 for a, b in ev[layers:]]
+        out[label] = {"bytes": nb, "us": round(float(np.mean(us)), 2),
+                      "gbps": round(nb / (float(np.mean(us)) * 1e-6) / 1e9, 1)}
+        del buf
+    return out
+
+
 def pmc_probe(device, reps=3, mib=256):
     """Plain copies of known size, so that traffic counters can be calibrated in the same run."""
     import torch
@@ -421,6 +450,10 @@ def main():
         out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
         out["roofline"]["traffic_source"] = "profiles/pmc_traffic_stress.json (rocprofv3 --pmc " \
                                             "FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size)"
+    sp = stream_probe(device, s["alg_bytes_per_launch"])
+    out["roofline"]["plain_streaming_kernel"] = sp
+    out["roofline"]["frac_of_plain_streaming_same_bytes"] = round(
+        s["kv_gbps"] / sp["same_bytes"]["gbps"], 4)
     if args.pmc_probe:
         out["pmc_probe_bytes"] = pmc_probe(device)
     if not args.no_cross_task:

@@ -218,6 +218,12 @@ int32_t oxy_batch_work(const oxy_batch *batch, int32_t *out, int32_t cap_items);
  * dst (both DEVICE), enqueued on hip_stream.  It moves a known number of bytes, so hardware
  * traffic counters read during it calibrate the same counters read during the attention launch. */
 int32_t oxy_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
+/* Measurement aid: a read-only streaming pass over `bytes` (multiple of 32 KiB) of src (DEVICE):
+ * every wavefront pulls two 16 KiB blocks with all its loads in flight and folds them into a
+ * value it never stores (sink, DEVICE, >= 16 bytes, is written only in a case that cannot occur).
+ * Timed next to the attention launch it gives the rate a plain streaming kernel reaches on this
+ * machine for the same number of bytes per launch. */
+int32_t oxy_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
 
 const char *oxy_last_error(void);
 int32_t oxy_version(void);

@@ -28,7 +28,7 @@ EXPORTS = [
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
-    "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe",
+    "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe", "oxy_read_probe",
 ]
 
 
@@ -102,6 +102,7 @@ def lib():
             "oxy_batch_slots": [vp, ctypes.POINTER(ctypes.c_int64), i32],
             "oxy_batch_work": [vp, pi32, i32],
             "oxy_copy_probe": [vp, vp, ctypes.c_size_t, vp],
+            "oxy_read_probe": [vp, ctypes.c_size_t, vp, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -306,3 +307,7 @@ def oxy_batch_work(batch):
 
 def oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream):
     _check(lib().oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream or None))
+
+
+def oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream):
+    _check(lib().oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream or None))

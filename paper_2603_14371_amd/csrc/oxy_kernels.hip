@@ -746,4 +746,27 @@ hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream
   return hipGetLastError();
 }
 
+// read-only streaming pass: one wavefront per 32 KiB, all 32 loads in flight
+__global__ __launch_bounds__(256, 2) void read_probe_kernel(const char* __restrict__ src,
+                                                            u32x4* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const char* p = src + wave * 32768 + lane * 16;
+  u32x4 v[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) v[i] = *(const u32x4*)(p + i * 1024);
+  u32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+  for (int i = 0; i < 32; ++i) acc ^= v[i];
+  if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0xf39cc060u && acc[3] == 0x5cedc834u)
+    sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
+hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s) {
+  const size_t n = bytes / (4 * 32768);
+  if (n == 0) return hipSuccess;
+  read_probe_kernel<<<(unsigned)n, 256, 0, s>>>((const char*)src, (u32x4*)sink);
+  return hipGetLastError();
+}
+
 }  // namespace oxy

@@ -844,6 +844,14 @@ int32_t oxy_copy_probe(void* dst, const void* src, size_t bytes, void* hip_strea
   return OXY_OK;
 }
 
+int32_t oxy_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || bytes == 0 || (bytes % (4 * 32768)))
+    return fail(OXY_ERR_INVALID_ARG, "read_probe: null or bytes not a multiple of 128 KiB");
+  hipError_t e = oxy::launch_read_probe(src, bytes, sink, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "read_probe: launch");
+  return OXY_OK;
+}
+
 // ---- introspection ------------------------------------------------------------------------
 int32_t oxy_stream_info(oxy_pool* p, int32_t sid, int32_t* prefix_id, int32_t* kind,
                         int32_t* own_len, int32_t* n_blocks) {
