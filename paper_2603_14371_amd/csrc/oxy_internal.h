@@ -48,8 +48,8 @@ struct AttnArgs {
   const int32_t* tables;
   const int32_t* part_off;  // [n_q]
   const int32_t* n_parts;   // [n_q]
-  float* part_acc;          // [n_partials][8][256]
-  float* part_ml;           // [n_partials][8][2]  (running max in log2 domain, sum)
+  uint16_t* part_acc;       // [n_partials][8][256] fp16: accumulator / row scale
+  float* part_ml;           // [n_partials][8][4]: reference max (log2 domain), sum, row scale, -
   int32_t n_work;
   int32_t n_q;
   float scale;

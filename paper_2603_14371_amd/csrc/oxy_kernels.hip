@@ -50,6 +50,20 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// two floats -> packed fp16 pair (round to nearest even)
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+  typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2;
+  typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_;
+  const f32x2_ f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+}
+__device__ __forceinline__ void unpack_f16(uint32_t u, float& lo, float& hi) {
+  typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2;
+  const f16x2 h = __builtin_bit_cast(f16x2, u);
+  lo = (float)h[0];
+  hi = (float)h[1];
+}
+
 // max over the four lanes {n, n+16, n+32, n+48} that hold one query row: two register swaps
 // between lane halves (v_permlane16_swap, v_permlane32_swap), no LDS round trip
 __device__ __forceinline__ float row_max4(float x) {
@@ -433,15 +447,26 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   DBG_MARK(3);
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
+  // The partial leaves as (m, l, scale, acc / scale in fp16): half the bytes of fp32, and the
+  // per-row scale (max |acc| of the row) keeps it independent of the magnitude of the values.
+  float amax = 0.f;
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(acc[c][e]));
+  amax = row_max4(amax);
+  const float inv = amax > 0.f ? 1.f / amax : 0.f;
   if (row_valid) {
     const size_t slot = (size_t)a.part_off[tok] + wi.part_idx;
-    float* dst = a.part_acc + (slot * kHeads + h) * kDim;
+    uint16_t* dst = a.part_acc + (slot * kHeads + h) * kDim;
+    typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) *(f32x4*)(dst + 16 * c + 4 * g) = acc[c];
-    if (g == 0) {
-      a.part_ml[(slot * kHeads + h) * 2] = m;
-      a.part_ml[(slot * kHeads + h) * 2 + 1] = l;
+    for (int c = 0; c < 16; ++c) {
+      const u32x2 v = {pack_f16(acc[c][0] * inv, acc[c][1] * inv),
+                       pack_f16(acc[c][2] * inv, acc[c][3] * inv)};
+      *(u32x2*)(dst + 16 * c + 4 * g) = v;
     }
+    if (g == 0) *(f32x4*)(a.part_ml + (slot * kHeads + h) * 4) = (f32x4){m, l, amax, 0.f};
   }
 }
 
@@ -565,22 +590,33 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       total = __builtin_fmaf(wgt[w], sml[w][r][1], total);
     }
     const size_t slot = (size_t)a.part_off[otok] + wi.part_idx;
-    float* dst = a.part_acc + (slot * kHeads + (r & 7)) * kDim + seg;
+    uint16_t* dst = a.part_acc + (slot * kHeads + (r & 7)) * kDim + seg;
+    f32x4 o[4];
+    float amax = 0.f;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      f32x4 o = {0.f, 0.f, 0.f, 0.f};
+      o[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const f32x4 x = *(const f32x4*)(sm + (w * 16 + r) * kMergeStride + seg + 4 * q);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt[w], x[e], o[e]);
+        for (int e = 0; e < 4; ++e) o[q][e] = __builtin_fmaf(wgt[w], x[e], o[q][e]);
       }
-      *(f32x4*)(dst + 4 * q) = o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(o[q][e]));
     }
-    if ((tid & 15) == 0) {
-      a.part_ml[(slot * kHeads + (r & 7)) * 2] = big;
-      a.part_ml[(slot * kHeads + (r & 7)) * 2 + 1] = total;
-    }
+    // row scale over the 16 threads that hold this row (the branch is uniform per wavefront)
+#pragma unroll
+    for (int sh = 1; sh < 16; sh <<= 1) amax = fmaxf(amax, __shfl_xor(amax, sh));
+    const float inv = amax > 0.f ? 1.f / amax : 0.f;
+    const u32x4 lo = {pack_f16(o[0][0] * inv, o[0][1] * inv), pack_f16(o[0][2] * inv, o[0][3] * inv),
+                      pack_f16(o[1][0] * inv, o[1][1] * inv), pack_f16(o[1][2] * inv, o[1][3] * inv)};
+    const u32x4 hi = {pack_f16(o[2][0] * inv, o[2][1] * inv), pack_f16(o[2][2] * inv, o[2][3] * inv),
+                      pack_f16(o[3][0] * inv, o[3][1] * inv), pack_f16(o[3][2] * inv, o[3][3] * inv)};
+    *(u32x4*)(dst) = lo;
+    *(u32x4*)(dst + 8) = hi;
+    if ((tid & 15) == 0)
+      *(f32x4*)(a.part_ml + (slot * kHeads + (r & 7)) * 4) = (f32x4){big, total, amax, 0.f};
   }
 }
 
@@ -625,9 +661,9 @@ extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
 #endif
 
 // ------------------------------------------------------------------------------------------
-// merge of a query token's partials (log-sum-exp rule).  Two workgroups per token (four heads
-// each); a thread owns four consecutive output dims of one head and has every load of the first
-// sixteen partials in flight at once.
+// merge of a query token's partials (log-sum-exp rule).  One workgroup per token; a thread owns
+// eight consecutive output dims of one head and has every load of the first sixteen partials in
+// flight at once.
 // (A merge fused into attn_kernel by "last arriver merges" was built twice and measured: with
 // device-scope fences every workgroup pays a whole-L2 write-back + invalidate (165 us per
 // launch); with scoped write-through stores and no fences it is correct and fence-free, but the
@@ -636,47 +672,53 @@ extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
 // ------------------------------------------------------------------------------------------
 constexpr int kMergeAhead = 16;   // partials whose loads are all issued before anything is used
 
-__device__ __forceinline__ void merge_block(const AttnArgs& a, const int block) {
-  const int tok = block >> 1, t = threadIdx.x;
-  const int h = ((block & 1) << 2) | (t >> 6), d0 = (t & 63) * 4;
+// One workgroup per token; thread t owns head t/32 and eight consecutive output dims.
+__device__ __forceinline__ void merge_block(const AttnArgs& a, const int tok) {
+  const int t = threadIdx.x;
+  const int h = t >> 5, d0 = (t & 31) * 8;
   const int np = a.n_parts[tok];
   const size_t base = (size_t)a.part_off[tok];
-  typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
-  const float* ml = a.part_ml + (base * kHeads + h) * 2;
-  const float* src = a.part_acc + (base * kHeads + h) * kDim + d0;
+  const float* ml = a.part_ml + (base * kHeads + h) * 4;
+  const uint16_t* src = a.part_acc + (base * kHeads + h) * kDim + d0;
   const size_t stride = (size_t)kHeads * kDim;
   const float ninf = -__builtin_inff();
   // one round trip for the common case: every load of the first 16 partials is in flight at once
-  f32x4 x[kMergeAhead];
-  f32x2 w[kMergeAhead];
+  u32x4 x[kMergeAhead];
+  f32x4 w[kMergeAhead];
 #pragma unroll
   for (int u = 0; u < kMergeAhead; ++u) {
     const int p = u < np ? u : 0;
-    x[u] = *(const f32x4*)(src + (size_t)p * stride);
-    w[u] = *(const f32x2*)(ml + (size_t)p * kHeads * 2);
+    x[u] = *(const u32x4*)(src + (size_t)p * stride);
+    w[u] = *(const f32x4*)(ml + (size_t)p * kHeads * 4);
   }
   float big = ninf;
 #pragma unroll
   for (int u = 0; u < kMergeAhead; ++u) big = fmaxf(big, u < np ? w[u][0] : ninf);
-  for (int p = kMergeAhead; p < np; ++p) big = fmaxf(big, ml[(size_t)p * kHeads * 2]);
+  for (int p = kMergeAhead; p < np; ++p) big = fmaxf(big, ml[(size_t)p * kHeads * 4]);
   float total = 0.f;
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  auto add = [&](const float mp, const float lp, const f32x4& v) {
-    const float wgt = (mp == ninf) ? 0.f : fast_exp2(mp - big);
-    total = __builtin_fmaf(wgt, lp, total);
+  float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto add = [&](const f32x4& mls, const u32x4& v) {   // mls = (m, l, scale, -)
+    const float wgt = (mls[0] == ninf) ? 0.f : fast_exp2(mls[0] - big);
+    total = __builtin_fmaf(wgt, mls[1], total);
+    const float ws = wgt * mls[2];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(wgt, v[e], o[e]);
+    for (int i = 0; i < 4; ++i) {
+      float lo, hi;
+      unpack_f16(v[i], lo, hi);
+      o[2 * i] = __builtin_fmaf(ws, lo, o[2 * i]);
+      o[2 * i + 1] = __builtin_fmaf(ws, hi, o[2 * i + 1]);
+    }
   };
 #pragma unroll
   for (int u = 0; u < kMergeAhead; ++u)
-    if (u < np) add(w[u][0], w[u][1], x[u]);
+    if (u < np) add(w[u], x[u]);
   for (int p = kMergeAhead; p < np; ++p)
-    add(ml[(size_t)p * kHeads * 2], ml[(size_t)p * kHeads * 2 + 1], *(const f32x4*)(src + (size_t)p * stride));
+    add(*(const f32x4*)(ml + (size_t)p * kHeads * 4), *(const u32x4*)(src + (size_t)p * stride));
   const float inv = 1.f / total;
-  typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
-  const u32x2 packed = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
-  *(u32x2*)((uint16_t*)a.out + ((size_t)tok * kHeads + h) * kDim + d0) = packed;
-  if (a.lse && (t & 63) == 0)
+  const u32x4 packed = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv),
+                        pack_bf16(o[4] * inv, o[5] * inv), pack_bf16(o[6] * inv, o[7] * inv)};
+  *(u32x4*)((uint16_t*)a.out + ((size_t)tok * kHeads + h) * kDim + d0) = packed;
+  if (a.lse && (t & 31) == 0)
     a.lse[(size_t)tok * kHeads + h] = (big + __builtin_amdgcn_logf(total)) * 0.6931471805599453f;
 }
 
@@ -685,7 +727,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) { merge_bl
 // merge of one layer and, in the same launch, the append of the next layer's new rows (the two
 // touch disjoint memory: partials/outputs of layer l, pool slots of layer l+1)
 __global__ __launch_bounds__(256) void merge_append_kernel(const AttnArgs a, const AppendArgs nx) {
-  const int n_merge = 2 * a.n_q;
+  const int n_merge = a.n_q;
   if ((int)blockIdx.x < n_merge) {
     merge_block(a, blockIdx.x);
   } else {
@@ -711,16 +753,16 @@ hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStr
   if (a.n_q <= 0) return hipErrorInvalidValue;
   const bool timed = start || stop;
   if (next && next->n_tokens > 0) {
-    const dim3 grid(2 * a.n_q + next->n_tokens);
+    const dim3 grid(a.n_q + next->n_tokens);
     if (timed)
       hipExtLaunchKernelGGL(merge_append_kernel, grid, dim3(256), 0, s, start, stop, 0, a, *next);
     else
       merge_append_kernel<<<grid, 256, 0, s>>>(a, *next);
   } else {
     if (timed)
-      hipExtLaunchKernelGGL(merge_kernel, dim3(2 * a.n_q), dim3(256), 0, s, start, stop, 0, a);
+      hipExtLaunchKernelGGL(merge_kernel, dim3(a.n_q), dim3(256), 0, s, start, stop, 0, a);
     else
-      merge_kernel<<<2 * a.n_q, 256, 0, s>>>(a);
+      merge_kernel<<<a.n_q, 256, 0, s>>>(a);
   }
   return hipGetLastError();
 }

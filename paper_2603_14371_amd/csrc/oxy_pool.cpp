@@ -127,8 +127,8 @@ size_t desc_words_of(const oxy_pool_config& c) {
 
 void layout_of(const oxy_pool_config& c, size_t* acc_off, size_t* ml_off, size_t* total) {
   size_t desc = align_up(desc_words_of(c) * 4, 256);
-  size_t acc = (size_t)c.max_partials * oxy::kHeads * oxy::kDim * sizeof(float);
-  size_t ml = align_up((size_t)c.max_partials * oxy::kHeads * 2 * sizeof(float), 256);
+  size_t acc = align_up((size_t)c.max_partials * oxy::kHeads * oxy::kDim * sizeof(uint16_t), 256);
+  size_t ml = align_up((size_t)c.max_partials * oxy::kHeads * 4 * sizeof(float), 256);
   *acc_off = desc;
   *ml_off = desc + acc;
   *total = desc + acc + ml;
@@ -732,7 +732,7 @@ oxy::AttnArgs attn_args(const oxy_pool* p, const oxy_batch* b, int32_t layer, co
   a.tables = d + b->off_tables;
   a.part_off = d + b->off_part_off;
   a.n_parts = d + b->off_n_parts;
-  a.part_acc = (float*)(ds.d_base + p->acc_offset);
+  a.part_acc = (uint16_t*)(ds.d_base + p->acc_offset);
   a.part_ml = (float*)(ds.d_base + p->ml_offset);
   a.n_work = b->n_work;
   a.n_q = b->n_tokens;
