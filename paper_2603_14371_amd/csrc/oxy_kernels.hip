@@ -650,6 +650,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
     g_dbg[blockIdx.x * 16 + 5] = path;
     g_dbg[blockIdx.x * 16 + 6] = (wi.kv_end - wi.kv_begin + 31) >> 5;
     g_dbg[blockIdx.x * 16 + 7] = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);  // XCC_ID
+    g_dbg[blockIdx.x * 16 + 14] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);  // HW_ID
   }
 #endif
 }

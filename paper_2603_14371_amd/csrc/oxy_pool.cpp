@@ -523,7 +523,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     // (longest-processing-time rule over the groups).  Padding records keep the pattern intact.
     {
       const int32_t nw = (int32_t)(hdr.size() / kHdr);
-      constexpr int kXcd = 8;
+      constexpr int kXcd = 8, kCuPerXcd = 32;
       struct Rec {
         int64_t key;     // tiles: (table, split begin); streaming items: unique
         int32_t idx, cost;
@@ -572,6 +572,19 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         std::stable_sort(queue[x].begin(), queue[x].end(), [](const Rec& a, const Rec& b) {
           return a.cost != b.cost ? a.cost > b.cost : a.idx < b.idx;
         });
+        // Inside an XCD the dispatcher hands workgroups to the 32 CUs in turn, so while at most
+        // two are resident per CU, positions j and j + 32 of a class share a CU, and a CU's
+        // share of the memory system is what bounds its workgroups.  Pair the largest of the
+        // first round with the smallest of the second; first-round items without a partner are
+        // the largest ones.  Anything past 64 follows in descending order (it back-fills).
+        std::vector<Rec>& q = queue[x];
+        if (q.size() > (size_t)kCuPerXcd) {
+          const size_t top = std::min(q.size(), (size_t)2 * kCuPerXcd), m = top - kCuPerXcd;
+          const std::vector<Rec> r(q.begin(), q.begin() + top);
+          for (size_t j = 0; j < m; ++j) q[j] = r[kCuPerXcd - m + j];
+          for (size_t j = m; j < (size_t)kCuPerXcd; ++j) q[j] = r[j - m];
+          for (size_t j = 0; j < m; ++j) q[kCuPerXcd + j] = r[top - 1 - j];
+        }
         longest = std::max(longest, queue[x].size());
       }
       order.reserve(longest * kXcd);
