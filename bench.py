@@ -86,17 +86,19 @@ class StepRunner:
         self.stream = torch.cuda.current_stream(device).cuda_stream
         self.n_tok = n_tok
 
-    def step(self, items, events=None, fuse=False):
+    def step(self, items, events=None, mode="fold"):
         """One whole step: batch build, then append + attention for every layer (the per-layer
-        loop runs below the ABI in oxy_step_layers).  fuse: let the merge of layer l share a
-        launch with the append of layer l+1 (all layers' K/V are resident here)."""
+        loop runs below the ABI in oxy_step_layers).  mode: "fold" = the attention work items
+        write the new rows themselves (two launches per layer), "separate" = append, work items,
+        merge (three launches), "fuse" = the merge of layer l shares a launch with the append of
+        layer l+1 (only possible because all layers' K/V are resident here)."""
         from paper_2603_14371_amd import binding as B
         gw = self.gw
+        flags = {"fold": B.STEP_FOLD_APPEND, "separate": 0, "fuse": B.STEP_FUSE_ACROSS_LAYERS}[mode]
         batch = B.oxy_batch_build(gw.pool, items, 0, self.stream)
         B.oxy_step_layers(gw.pool, batch, 0, self.L, self.k.data_ptr(), self.v.data_ptr(),
                           self.k.stride(0) * 2, self.q.data_ptr(), self.o.data_ptr(),
-                          self.q.stride(0) * 2, 0, 0, gw.scale,
-                          B.STEP_FUSE_ACROSS_LAYERS if fuse else 0, events, self.stream)
+                          self.q.stride(0) * 2, 0, 0, gw.scale, flags, events, self.stream)
         B.oxy_batch_destroy(batch)
 
 
@@ -138,7 +140,7 @@ def _live_kv_tokens(gw, items):
 def bench_stress(args, device):
     import torch
     from paper_2603_14371_amd import synth
-    w = synth.stress(mixed_steps=args.warmup + 3 * args.steps + 2)
+    w = synth.stress(mixed_steps=args.warmup + 4 * args.steps + 2)
     t0 = time.time()
     gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens)
     setup_s = time.time() - t0
@@ -169,13 +171,16 @@ def bench_stress(args, device):
         runner.step(steps[args.warmup + args.steps + i]["items"], sets[i].raw)
     torch.cuda.synchronize(device)
     step_us_ev = (time.perf_counter() - t_start) / args.steps * 1e6
-    # ---- and once more with the cross-layer launch fusion (merge l + append l+1 in one launch)
-    torch.cuda.synchronize(device)
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        runner.step(steps[args.warmup + 2 * args.steps + i]["items"], fuse=True)
-    torch.cuda.synchronize(device)
-    step_us_fused = (time.perf_counter() - t_start) / args.steps * 1e6
+    # ---- and with the other launch schedules: three launches per layer, and the cross-layer
+    # fusion (merge l + append l+1 in one launch)
+    other = {}
+    for j, mode in enumerate(("separate", "fuse")):
+        torch.cuda.synchronize(device)
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            runner.step(steps[args.warmup + (2 + j) * args.steps + i]["items"], mode=mode)
+        torch.cuda.synchronize(device)
+        other[mode] = (time.perf_counter() - t_start) / args.steps * 1e6
     attn_us = [t for es in sets for t in es.work_us()]
     attn_avg_us = float(np.mean(attn_us))
     merge_avg_us = float(np.mean([t for es in sets for t in es.merge_us()]))
@@ -186,7 +191,8 @@ def bench_stress(args, device):
     res = {
         "step_us": step_us,
         "step_us_with_events": step_us_ev,
-        "step_us_fused": step_us_fused,
+        "step_us_separate": other["separate"],
+        "step_us_fused": other["fuse"],
         "attn_launch_us": attn_avg_us,
         "merge_launch_us": merge_avg_us,
         "alg_bytes_per_launch": alg_bytes,
@@ -442,7 +448,10 @@ def main():
                      "merge_launch_us": round(s["merge_launch_us"], 2),
                      "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
     }
+    out["launch_schedule"] = "per layer: work items (new rows appended by the work items " \
+                             "themselves) + merge"
     out["step_us_with_events"] = round(s["step_us_with_events"], 2)
+    out["step_us_three_launches_per_layer"] = round(s["step_us_separate"], 2)
     out["step_us_merge_append_fused_across_layers"] = round(s["step_us_fused"], 2)
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
     if os.path.exists(traffic_file):

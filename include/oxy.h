@@ -180,15 +180,28 @@ int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t laye
  * when layer l+1's K/V depend on layer l's output.  OXY_STEP_FUSE_ACROSS_LAYERS = the merge of
  * layer l shares its launch with the append of layer l+1 (disjoint memory); only meaningful when
  * every layer's new K/V is known up front (attention-only replay, benchmarking).
+ * OXY_STEP_FOLD_APPEND = the work items themselves write the new rows (two launches per layer):
+ * a decode item's new token is read only by the work item that owns the last split of its own
+ * history, so that work item writes it first; an item whose own history was empty before the
+ * step (an action chunk, Sec. 3.2: its K/V live for one denoise step) reads its keys from
+ * k_new / v_new directly and writes them to the pool on the side.  Outputs and pool contents
+ * are those of flags = 0.  A batch with an item of more than 2 new tokens on a non-empty own
+ * history is not covered; for it the flag is ignored.  Wins over OXY_STEP_FUSE_ACROSS_LAYERS.
  * events: NULL, or HOST array of 4*(layer_end-layer_begin) created hipEvent_t; per layer they
  * receive the begin and end timestamps of the work-item kernel and of the merge kernel
  * themselves (hipExtLaunchKernel start/stop events; a profiling hook). */
-enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1 };
+enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1, OXY_STEP_FOLD_APPEND = 2 };
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,
                         size_t kv_layer_stride, const void *q, void *out, size_t q_layer_stride,
                         float *lse, size_t lse_layer_stride, float scale, int32_t flags,
                         void *const *events, void *hip_stream);
+/* oxy_stream_append + oxy_mixed_attention of one layer in two launches instead of three: the
+ * KV part of Update (App. A.2) folded into the attention work items, see OXY_STEP_FOLD_APPEND.
+ * k_new, v_new: DEVICE bf16 [n_tokens][256] of this layer; q, out, lse as oxy_mixed_attention. */
+int32_t oxy_append_attention(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
+                             const void *k_new, const void *v_new, const void *q, void *out,
+                             float *lse, float scale, void *hip_stream);
 int32_t oxy_batch_destroy(oxy_batch *batch);
 
 /* Reads K/V rows back in natural order: slots HOST int64 [n] (block*16+offset);

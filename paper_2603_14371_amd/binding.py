@@ -19,12 +19,14 @@ KIND_ACTION, KIND_DECODE = 0, 1
 POOL_HOST_ONLY = 1
 BATCH_APPEND_ONLY = 1
 STEP_FUSE_ACROSS_LAYERS = 1
+STEP_FOLD_APPEND = 2
 
 EXPORTS = [
     "oxy_version", "oxy_last_error", "oxy_kv_bytes", "oxy_workspace_bytes", "oxy_pool_create",
     "oxy_pool_destroy", "oxy_prefix_create", "oxy_prefix_append", "oxy_prefix_release",
     "oxy_stream_create", "oxy_stream_release", "oxy_stream_rewind", "oxy_batch_build",
-    "oxy_stream_append", "oxy_mixed_attention", "oxy_step_layers", "oxy_batch_destroy",
+    "oxy_stream_append", "oxy_mixed_attention", "oxy_step_layers", "oxy_append_attention",
+    "oxy_batch_destroy",
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
@@ -89,6 +91,7 @@ def lib():
             "oxy_mixed_attention": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
             "oxy_step_layers": [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp, ctypes.c_size_t,
                                 vp, ctypes.c_size_t, ctypes.c_float, i32, ctypes.POINTER(vp), vp],
+            "oxy_append_attention": [vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp],
             "oxy_batch_destroy": [vp],
             "oxy_gather_kv": [vp, i32, ctypes.POINTER(ctypes.c_int64), i32, vp, vp, vp],
             "oxy_stream_info": [vp, i32, pi32, pi32, pi32, pi32],
@@ -213,6 +216,11 @@ def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_
     _check(lib().oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride,
                                  q_ptr, out_ptr, q_layer_stride, lse_ptr or None, lse_layer_stride,
                                  ctypes.c_float(scale), flags, events, stream or None))
+
+
+def oxy_append_attention(pool, batch, layer, k_ptr, v_ptr, q_ptr, out_ptr, lse_ptr, scale, stream):
+    _check(lib().oxy_append_attention(pool, batch, layer, k_ptr, v_ptr, q_ptr, out_ptr,
+                                      lse_ptr or None, ctypes.c_float(scale), stream or None))
 
 
 def oxy_batch_destroy(batch):

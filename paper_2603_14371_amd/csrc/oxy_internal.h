@@ -23,6 +23,10 @@ enum { W_TOK_OFF = 0, W_N_TOK, W_TBL_OFF, W_KV_BEGIN, W_KV_END, W_CAUSAL_Q0, W_P
 enum { PATH_STREAM = 0,  // <=2 query tokens (16 rows): 4 wavefronts split the keys, KV to registers
        PATH_TILE = 1,    // <=8 query tokens (64 rows): 4 wavefronts share the keys through LDS
        PATH_NOOP = 2 };  // padding that keeps the index -> XCD pattern of the work list intact
+// The path sits in the low four bits of word W_PATH.  kPathFresh marks an own-phase tile of an
+// item whose own history was empty before this step: all of its keys are rows of this step's
+// k_new / v_new, row = (word >> kPathRowShift) + own position.
+constexpr int kPathMask = 15, kPathFresh = 16, kPathRowShift = 8;
 
 struct InlineIds {
   int32_t v[kMaxInlineBlocks];
@@ -53,6 +57,13 @@ struct AttnArgs {
   int32_t n_work;
   int32_t n_q;
   float scale;
+  // Append folded into the work items (all three null otherwise): this step's new rows
+  // [n_q][256] bf16 and their slots.  A streaming work item first writes the new rows that lie
+  // in its key range into the pool; a fresh tile reads its keys from the new rows themselves
+  // and the tile of split 0 writes its own query tokens' rows.
+  const void* k_new;
+  const void* v_new;
+  const int32_t* d_slots;
 };
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);       // work items, then merge
 // work items only; start/stop (may be null) receive the kernel's own begin/end timestamps

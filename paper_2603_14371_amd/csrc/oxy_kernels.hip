@@ -91,15 +91,32 @@ __device__ __forceinline__ int v_slot_of_key(int key) { return ((key >> 3) << 2)
 // ------------------------------------------------------------------------------------------
 // append / gather
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void append_row(const uint16_t* __restrict__ k_row,
-                                           const uint16_t* __restrict__ v_row, int32_t slot,
-                                           char* __restrict__ layer_base, int t) {
+// One row of K and V on its way into a page: thread t of 256 carries 16 bytes of K (t < 32)
+// and one element of V.  Load and store are separate so that callers can keep several rows in
+// flight before the first store.
+struct RowPart {
+  u32x4 k;
+  uint16_t v;
+};
+__device__ __forceinline__ RowPart load_row(const uint16_t* __restrict__ k_row,
+                                            const uint16_t* __restrict__ v_row, int t) {
+  RowPart r;
+  r.k = *(const u32x4*)(k_row + (t & 31) * 8);
+  r.v = v_row[t];
+  return r;
+}
+__device__ __forceinline__ void store_row(const RowPart& r, int32_t slot,
+                                          char* __restrict__ layer_base, int t) {
   const int blk = slot >> 4, key = slot & 15;
   char* kp = layer_base + (size_t)blk * kBlockBytes;
   char* vp = kp + kPageBytes;
-  if (t < 32)
-    *(u32x4*)(kp + k_chunk_offset(t >> 2, key >> 3, t & 3, key & 7)) = *(const u32x4*)(k_row + t * 8);
-  *(uint16_t*)(vp + v_chunk_offset(t >> 4, (key >> 2) & 1, t & 15) + v_slot_of_key(key) * 2) = v_row[t];
+  if (t < 32) *(u32x4*)(kp + k_chunk_offset(t >> 2, key >> 3, t & 3, key & 7)) = r.k;
+  *(uint16_t*)(vp + v_chunk_offset(t >> 4, (key >> 2) & 1, t & 15) + v_slot_of_key(key) * 2) = r.v;
+}
+__device__ __forceinline__ void append_row(const uint16_t* __restrict__ k_row,
+                                           const uint16_t* __restrict__ v_row, int32_t slot,
+                                           char* __restrict__ layer_base, int t) {
+  store_row(load_row(k_row, v_row, t), slot, layer_base, t);
 }
 
 __global__ __launch_bounds__(256) void append_kernel(const uint16_t* __restrict__ k_new,
@@ -305,7 +322,11 @@ __device__ __forceinline__ int split_block_ids(const WorkItem& wi, const int lan
 
 // ---- tile path: <= 8 query tokens (64 rows); the four wavefronts share every KV page through
 // LDS (double-buffered, one barrier per 32-key step) and own 16 rows each.
-__device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi, char* smem) {
+// kFresh: the keys are rows of this step's k_new / v_new (row0 + own position) instead of pool
+// pages; they are brought into the same register image, so everything after the fetch is shared.
+template <bool kFresh>
+__device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi, char* smem,
+                                          const int row0) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int n = lane & 15, g = lane >> 4;
@@ -336,6 +357,35 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   // same 16 B per thread); a missing page B re-reads page A.  Neither is ever used.
   auto fetch = [&](const int s, u32x4 (&st)[8]) {
     const bool real = s < nsteps;
+    if constexpr (kFresh) {
+      // thread tid holds chunks tid and tid+256 of each page: K chunk = 8 dims of one key (one
+      // 16-byte load from the row), V chunk = one dim of 8 keys (eight 2-byte loads).  Positions
+      // at or beyond the split's end re-read its last row; they are masked like stale slots.
+      const int pos0 = wi.kv_begin + (real ? 32 * s : 0), last = wi.kv_end - 1;
+      const uint16_t* kn = (const uint16_t*)a.k_new + (size_t)row0 * kDim;
+      const uint16_t* vn = (const uint16_t*)a.v_new + (size_t)row0 * kDim;
+      const int kkey = ((tid >> 5) & 1) * 8 + (tid & 7);
+      const int kdim = (tid >> 6) * 32 + ((tid >> 3) & 3) * 8;
+      const int gp = (tid >> 4) & 1, vdim = (tid >> 5) * 16 + (tid & 15);
+#pragma unroll
+      for (int pgi = 0; pgi < 2; ++pgi) {
+        const uint16_t* ksrc = kn + (size_t)min(pos0 + 16 * pgi + kkey, last) * kDim + kdim;
+        st[2 * pgi] = *(const u32x4*)ksrc;
+        st[2 * pgi + 1] = *(const u32x4*)(ksrc + 128);
+        u32x4 lo, hi;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int k0 = pos0 + 16 * pgi + (i < 2 ? 4 * gp : 8 + 4 * gp) + 2 * (i & 1);
+          const uint16_t* r0 = vn + (size_t)min(k0, last) * kDim + vdim;
+          const uint16_t* r1 = vn + (size_t)min(k0 + 1, last) * kDim + vdim;
+          lo[i] = (uint32_t)r0[0] | ((uint32_t)r1[0] << 16);
+          hi[i] = (uint32_t)r0[128] | ((uint32_t)r1[128] << 16);
+        }
+        st[4 + 2 * pgi] = lo;
+        st[5 + 2 * pgi] = hi;
+      }
+      return;
+    }
     const int pi = real ? 2 * s : 0;                      // page index inside the split
     const int o = real ? 1 : 0;
     const int blk_a = __builtin_amdgcn_readlane(ids, pi);
@@ -425,6 +475,23 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     if (s == 3) DBG_MARK(12);
   };
   DBG_MARK(1);
+  // kFresh: the pool still has to receive the rows; the tile of split 0 writes its own query
+  // tokens'.  All eight rows are loaded first (the record repeats the last token id for a
+  // short tile), the stores follow once the first pages have been waited for anyway.
+  RowPart rows[kFresh ? 8 : 1];
+  int32_t row_slot[kFresh ? 8 : 1];
+  const bool writes_rows = kFresh && wi.kv_begin == 0;
+  if constexpr (kFresh) {
+    if (writes_rows) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
+        rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
+                           (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
+        row_slot[t] = a.d_slots[tk];
+      }
+    }
+  }
   fetch(0, st0);
   fetch(1, st1);
   {  // the query rows come after the first pages are on their way (they are needed later)
@@ -438,6 +505,13 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   __builtin_amdgcn_sched_barrier(0);
   sanitize(0, st0);
   commit(0, st0);
+  if constexpr (kFresh) {
+    if (writes_rows) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (t < wi.n_tok) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
+    }
+  }
   __syncthreads();
   DBG_MARK(2);
   for (int s = 0; s < nsteps; s += 2) {   // steps in pairs; a step past the end moves dummies
@@ -518,6 +592,36 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * o);
   };
   DBG_MARK(1);
+  // Folded append: the query tokens of a streaming item are its new rows.  Those inside this
+  // split's key range are written to the pool by this workgroup (no other workgroup reads
+  // them in this launch), and a workgroup barrier orders the writes before the page loads that
+  // cover them.  The first new row sits in step `first_new`: when that step is loaded after the
+  // barrier below anyway, the stores wait there; otherwise they go out, with a barrier of their
+  // own, before the first page load.
+  RowPart rows[2];
+  int32_t row_slot[2] = {0, 0};
+  bool row_mine[2] = {false, false};
+  bool early = false;
+  if (a.k_new) {
+    const int pos0 = (wi.q0 == kNoCausal ? 0 : wi.q0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int pos = pos0 + t;
+      row_mine[t] = t < wi.n_tok && pos >= wi.kv_begin && pos < wi.kv_end;
+      const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
+      rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
+                         (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
+      row_slot[t] = a.d_slots[tk];
+    }
+    const int first_new = (max(pos0, wi.kv_begin) - wi.kv_begin) >> 5;
+    early = first_new < 4;
+    if (early) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        if (row_mine[t]) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
+      __syncthreads();
+    }
+  }
   int s = wv;
   load_k(s);
   load_v(s);
@@ -532,6 +636,11 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       const int j = 2 * wv + jj;
       *(u32x4*)(qs + j * 1024 + lane * 16) = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
     }
+  }
+  if (a.k_new && !early) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (row_mine[t]) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
   }
   __syncthreads();
   const char* qf = qs + lane * 16;
@@ -634,11 +743,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   wi.kv_end = __builtin_amdgcn_readlane(wi.rec, W_KV_END);
   wi.q0 = __builtin_amdgcn_readlane(wi.rec, W_CAUSAL_Q0);
   wi.part_idx = __builtin_amdgcn_readlane(wi.rec, W_PART_IDX);
-  const int path = __builtin_amdgcn_readlane(wi.rec, W_PATH);
+  const int path_word = __builtin_amdgcn_readlane(wi.rec, W_PATH);
+  const int path = path_word & kPathMask;
   DBG_MARK(0);
   if (path == PATH_TILE) {
     __builtin_amdgcn_s_setprio(2);   // compute-heavy: issue ahead of co-resident streaming waves
-    tile_path(a, wi, smem);
+    if (a.k_new && (path_word & kPathFresh))
+      tile_path<true>(a, wi, smem, path_word >> kPathRowShift);
+    else
+      tile_path<false>(a, wi, smem, 0);
   } else if (path == PATH_STREAM) {
     stream_path(a, wi, smem, sml, qs);
   } else {

@@ -82,6 +82,7 @@ struct oxy_batch {
   int32_t slot = -1;
   int32_t flags = 0;
   int32_t n_items = 0, n_tokens = 0, n_work = 0, n_partials = 0;
+  bool append_foldable = false;   // every item has <= 2 new tokens or an empty own history
   // word offsets inside the descriptor
   int32_t off_slots = 0, off_work = 0, off_toks = 0, off_tables = 0, off_part_off = 0,
           off_n_parts = 0;
@@ -438,6 +439,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   std::vector<TableRef> table_refs;
   std::vector<int32_t> order;   // final order of the records; -1 = padding record
   int32_t tbl_words = 0;
+  bool foldable = !append_only;
   if (!append_only) {
     hdr.reserve(1024 * kHdr);
     toks.reserve(2 * n_tokens);
@@ -500,7 +502,13 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       tbl_words += blocks_for(pl.new_len);
       const int32_t n_new = pl.new_len - pl.old_len;
       const bool causal = pl.s->kind == OXY_KIND_DECODE;
-      const int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
+      int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
+      if (path == oxy::PATH_TILE) {
+        if (pl.old_len == 0)
+          path |= oxy::kPathFresh | (pl.tok0 << oxy::kPathRowShift);
+        else
+          foldable = false;   // old and new keys in one tile: only the separate append covers it
+      }
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
       const int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
@@ -532,7 +540,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       for (int32_t i = 0; i < nw; ++i) {
         const int32_t* r = &hdr[(size_t)i * kHdr];
         const int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
-        const bool tile = r[oxy::W_PATH] == oxy::PATH_TILE;
+        const bool tile = (r[oxy::W_PATH] & oxy::kPathMask) == oxy::PATH_TILE;
         recs[i].idx = i;
         recs[i].cost = tile ? 2 * steps : steps;
         recs[i].key = tile ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
@@ -637,6 +645,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   b->n_work = n_work;
   b->n_partials = (int32_t)n_partials;
   b->off_slots = 0;
+  b->append_foldable = foldable;
   b->off_work = b->off_slots + (int32_t)n_tokens;
   b->off_toks = b->off_work + n_work * oxy::kWorkWords;
   b->off_tables = b->off_toks + (int32_t)toks.size();
@@ -750,6 +759,8 @@ oxy::AttnArgs attn_args(const oxy_pool* p, const oxy_batch* b, int32_t layer, co
   a.n_work = b->n_work;
   a.n_q = b->n_tokens;
   a.scale = scale;
+  a.k_new = a.v_new = nullptr;
+  a.d_slots = nullptr;
   return a;
 }
 }  // namespace
@@ -772,14 +783,16 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
                         const void* q, void* out, size_t q_layer_stride, float* lse,
                         size_t lse_layer_stride, float scale, int32_t flags, void* const* events,
                         void* hip_stream) {
-  if (flags & ~OXY_STEP_FUSE_ACROSS_LAYERS) return fail(OXY_ERR_INVALID_ARG, "step_layers: flags");
-  const bool fuse = (flags & OXY_STEP_FUSE_ACROSS_LAYERS) != 0;
+  if (flags & ~(OXY_STEP_FUSE_ACROSS_LAYERS | OXY_STEP_FOLD_APPEND))
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: flags");
   if (!p || !b || b->pool != p || !k_new || !v_new || !q || !out || p->host_only)
     return fail(OXY_ERR_INVALID_ARG, "step_layers: null argument, foreign batch or host-only pool");
   if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
     return fail(OXY_ERR_INVALID_ARG, "step_layers: layers [%d, %d)", layer_begin, layer_end);
   if (b->flags & OXY_BATCH_APPEND_ONLY)
     return fail(OXY_ERR_INVALID_ARG, "step_layers: batch was built append-only");
+  const bool fold = (flags & OXY_STEP_FOLD_APPEND) != 0 && b->append_foldable;
+  const bool fuse = (flags & OXY_STEP_FUSE_ACROSS_LAYERS) != 0 && !fold;
   hipStream_t s = (hipStream_t)hip_stream;
   const int32_t* d_desc = (const int32_t*)p->slots[b->slot].d_base;
   auto append_of = [&](int32_t layer) {
@@ -791,8 +804,8 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     ap.layer_base = layer_base(p, layer);
     return ap;
   };
-  // Same kernels and the same order of effects as the per-layer calls.  With `fuse`, the merge
-  // of layer l and the append of layer l+1 (disjoint memory) share one launch.
+  // Same effects as the per-layer calls.  With `fuse`, the merge of layer l and the append of
+  // layer l+1 (disjoint memory) share one launch; with `fold`, the work items do the append.
   auto append_now = [&](int32_t layer) {
     oxy::AppendArgs ap = append_of(layer);
     return oxy::launch_append(ap.k_new, ap.v_new, ap.d_slots, ap.n_tokens, ap.layer_base, s);
@@ -804,7 +817,7 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
   for (int32_t layer = layer_begin; layer < layer_end; ++layer) {
     const size_t i = (size_t)(layer - layer_begin);
     hipError_t e = hipSuccess;
-    if (!fuse) {
+    if (!fuse && !fold) {
       e = append_now(layer);
       if (e != hipSuccess) return hip_fail(e, "step_layers: append");
     }
@@ -815,6 +828,12 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
                                 (char*)out + (size_t)layer * q_layer_stride,
                                 lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
                                 scale);
+    if (fold) {
+      const oxy::AppendArgs ap = append_of(layer);
+      a.k_new = ap.k_new;
+      a.v_new = ap.v_new;
+      a.d_slots = ap.d_slots;
+    }
     e = oxy::launch_attention_work(a, s, ev[0], ev[1]);
     if (e != hipSuccess) return hip_fail(e, "step_layers: attention");
     if (fuse && layer + 1 < layer_end) {
@@ -826,6 +845,17 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     if (e != hipSuccess) return hip_fail(e, "step_layers: merge");
   }
   return OXY_OK;
+}
+
+int32_t oxy_append_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* k_new,
+                             const void* v_new, const void* q, void* out, float* lse, float scale,
+                             void* hip_stream) {
+  if (layer < 0 || !p || layer >= p->cfg.n_layers)
+    return fail(OXY_ERR_INVALID_ARG, "append_attention: null pool or layer %d", layer);
+  // one layer of oxy_step_layers with the append folded in (layer strides 0: the pointers are
+  // this layer's own)
+  return oxy_step_layers(p, b, layer, layer + 1, k_new, v_new, 0, q, out, 0, lse, 0, scale,
+                         OXY_STEP_FOLD_APPEND, nullptr, hip_stream);
 }
 
 int32_t oxy_gather_kv(oxy_pool* p, int32_t layer, const int64_t* slots, int32_t n, void* k_out,
@@ -947,9 +977,11 @@ int32_t oxy_batch_slots(const oxy_batch* b, int64_t* out, int32_t cap) {
 
 int32_t oxy_batch_work(const oxy_batch* b, int32_t* out, int32_t cap_items) {
   if (!b || !out || cap_items < b->n_work) return fail(OXY_ERR_INVALID_ARG, "batch_work: cap");
-  for (int32_t i = 0; i < b->n_work; ++i)   // the eight header words of each record
+  for (int32_t i = 0; i < b->n_work; ++i) {   // the eight header words of each record
     std::copy(b->host.begin() + b->off_work + (size_t)i * oxy::kWorkWords,
               b->host.begin() + b->off_work + (size_t)i * oxy::kWorkWords + 8, out + (size_t)i * 8);
+    out[(size_t)i * 8 + oxy::W_PATH] &= oxy::kPathMask;
+  }
   return OXY_OK;
 }
 

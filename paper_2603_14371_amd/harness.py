@@ -36,7 +36,8 @@ class GpuWorld:
     def __init__(self, workload, data_fn=None, layers=None, device="cuda:0", split_tokens=0,
                  stream_split_tokens=0,
                  max_live_batches=2, max_q_tokens=None, max_append_tokens=None,
-                 max_work_items=0, max_partials=0, want_lse=True, poison=False):
+                 max_work_items=0, max_partials=0, want_lse=True, poison=False,
+                 fold_append=False):
         if not torch.cuda.is_available():
             raise RuntimeError("GpuWorld needs a GPU; there is no CPU fallback")
         w = workload
@@ -47,6 +48,7 @@ class GpuWorld:
         self.data_fn = data_fn
         self.scale = float(w["scale"])
         self.want_lse = want_lse
+        self.fold_append = fold_append     # one call per layer: append inside the attention
         mq, ma = trace_limits(w["trace"])
         cfg = B.make_config(self.n_layers, w["num_blocks"], free_order=w.get("free_order"),
                             max_live_batches=max_live_batches,
@@ -121,16 +123,22 @@ class GpuWorld:
             for layer in self.layers:
                 k = to_device_bf16(self.data_fn(op["data"], layer, "k", n_tok), self.device)
                 v = to_device_bf16(self.data_fn(op["data"], layer, "v", n_tok), self.device)
-                B.oxy_stream_append(self.pool, batch, layer, k.data_ptr(), v.data_ptr(),
-                                    self._stream())
+                if not (attend and self.fold_append):
+                    B.oxy_stream_append(self.pool, batch, layer, k.data_ptr(), v.data_ptr(),
+                                        self._stream())
                 if attend:
                     q = to_device_bf16(self.data_fn(op["data"], layer, "q", n_tok), self.device)
                     o = torch.empty_like(q)
                     lse = torch.empty((n_tok, 8), dtype=torch.float32, device=self.device) \
                         if self.want_lse else None
-                    B.oxy_mixed_attention(self.pool, batch, layer, q.data_ptr(), o.data_ptr(),
-                                          lse.data_ptr() if lse is not None else 0, self.scale,
-                                          self._stream())
+                    lse_ptr = lse.data_ptr() if lse is not None else 0
+                    if self.fold_append:
+                        B.oxy_append_attention(self.pool, batch, layer, k.data_ptr(), v.data_ptr(),
+                                               q.data_ptr(), o.data_ptr(), lse_ptr, self.scale,
+                                               self._stream())
+                    else:
+                        B.oxy_mixed_attention(self.pool, batch, layer, q.data_ptr(), o.data_ptr(),
+                                              lse_ptr, self.scale, self._stream())
                     torch.cuda.synchronize(self.device)
                     out["O"][layer] = bits_of(o)
                     if lse is not None:

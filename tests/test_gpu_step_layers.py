@@ -1,6 +1,6 @@
-"""oxy_step_layers (the per-layer loop of one step below the ABI, with the merge of layer l
-and the append of layer l+1 in one launch) must give bit for bit what the per-layer calls
-give: outputs, LSE and pool contents."""
+"""oxy_step_layers (the per-layer loop of one step below the ABI; optionally the merge of
+layer l and the append of layer l+1 in one launch, or the append folded into the work items)
+must give bit for bit what the per-layer calls give: outputs, LSE and pool contents."""
 import numpy as np
 import pytest
 
@@ -16,7 +16,7 @@ def test_step_layers_equals_per_layer_calls():
     w = synth.tiny(prefix_len=200, chunk=50, prior=77, n_layers=5)
     data = synth.DataSource(31337)
     results = {}
-    for mode in ("per_layer", "step_layers", "step_layers_fused"):
+    for mode in ("per_layer", "step_layers", "step_layers_fused", "step_layers_fold"):
         gw = GpuWorld(w, data, split_tokens=64)
         gw.run(w["trace"][:-1])                     # everything but the final mixed step
         op = w["trace"][-1]
@@ -38,7 +38,8 @@ def test_step_layers_equals_per_layer_calls():
             B.oxy_step_layers(gw.pool, batch, 0, L, k.data_ptr(), v.data_ptr(), k.stride(0) * 2,
                               q.data_ptr(), o.data_ptr(), q.stride(0) * 2, lse.data_ptr(),
                               lse.stride(0) * 4, gw.scale,
-                              B.STEP_FUSE_ACROSS_LAYERS if mode.endswith("fused") else 0, None, stream)
+                              {"step_layers": 0, "step_layers_fused": B.STEP_FUSE_ACROSS_LAYERS,
+                               "step_layers_fold": B.STEP_FOLD_APPEND}[mode], None, stream)
         torch.cuda.synchronize()
         B.oxy_batch_destroy(batch)
         pools = []
@@ -48,7 +49,7 @@ def test_step_layers_equals_per_layer_calls():
         results[mode] = (bits_of(o), lse.cpu().numpy(), pools)
         gw.close()
     a = results["per_layer"]
-    for other in ("step_layers", "step_layers_fused"):
+    for other in ("step_layers", "step_layers_fused", "step_layers_fold"):
         b = results[other]
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), other
         assert np.all(np.isfinite(b[1])) and np.any(b[0] != 0)
