@@ -175,6 +175,9 @@ def bench_stress(args, device):
     # fusion (merge l + append l+1 in one launch)
     other = {}
     for j, mode in enumerate(("separate", "fuse")):
+        if args.no_alt_schedules:
+            other[mode] = float("nan")
+            continue
         torch.cuda.synchronize(device)
         t_start = time.perf_counter()
         for i in range(args.steps):
@@ -408,6 +411,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-frame", action="store_true")
     ap.add_argument("--no-cross-task", action="store_true")
+    ap.add_argument("--no-alt-schedules", action="store_true",
+                    help="profiling aid: skip the passes with the other launch schedules")
     ap.add_argument("--only-frame", action="store_true",
                     help="profiling aid: run only the pi0.5-shaped frame section")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -451,8 +456,9 @@ def main():
     out["launch_schedule"] = "per layer: work items (new rows appended by the work items " \
                              "themselves) + merge"
     out["step_us_with_events"] = round(s["step_us_with_events"], 2)
-    out["step_us_three_launches_per_layer"] = round(s["step_us_separate"], 2)
-    out["step_us_merge_append_fused_across_layers"] = round(s["step_us_fused"], 2)
+    if not args.no_alt_schedules:
+        out["step_us_three_launches_per_layer"] = round(s["step_us_separate"], 2)
+        out["step_us_merge_append_fused_across_layers"] = round(s["step_us_fused"], 2)
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
     if os.path.exists(traffic_file):
         t = json.load(open(traffic_file))
