@@ -12,6 +12,8 @@ attention   float64 attention over the visible set of each query (numpy).
 brute       the same definition in pure-Python loops, for tiny cases.
 pool_model  the indexing oracle: free stack, refcounts, block tables, slots.
 replay      runs an operation trace through pool_model + attention.
+schedule    the per-frame execution flow (Alg. 1) under arbitrary arrivals, and the
+            ablation variants, as a plain simulation.
 
 Parity status: every function here is pinned by the non-GPU tests (brute force,
 closed forms, a library attention routine, the paper's shared == isolated
