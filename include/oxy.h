@@ -238,6 +238,55 @@ int32_t oxy_copy_probe(void *dst, const void *src, size_t bytes, void *hip_strea
  * machine for the same number of bytes per launch. */
 int32_t oxy_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
 
+/* --- frame scheduler: the per-frame execution flow (Alg. 1, App. A.3; Sec. 3.2) --------
+ * Host logic only.  Per frame: the caller appends the prefill KV of each new observation to a
+ * fresh prefix and admits it; the scheduler fans it out (Alg. 1 lines 2-5: an ACTION stream that
+ * is denoised over S steps, and a DECODE stream = a new language request under the next
+ * request id, App. A.2), then hands out the frame's steps one by one (lines 6-9): step s lists
+ * the chunk of every observation admitted in this frame while s < S and one token for every
+ * active request that has neither finished nor used up the per-frame budget k; the caller runs
+ * each step (oxy_batch_build, then append + attention per layer).  oxy_sched_end_frame evicts the
+ * finished requests and persists the rest (lines 10-13).  Any number of observations may
+ * arrive in a frame, also none (Sec. 4.4).  Termination is by length only (no logits here).
+ * mode (Sec. 4.3): OXY_SCHED_BATCHED = the flow above; OXY_SCHED_UNBATCHED = cross-task sharing
+ * without cross-frame batching: observations are served one after the other and each request
+ * runs to completion inside its frame; OXY_SCHED_UPPER_BOUND = the single-frame decoding oracle
+ * of the ablation: k tokens, then the request is dropped at frame end.
+ * Items of a step: action chunks in admission order, then requests in ascending id. */
+typedef struct oxy_sched oxy_sched;
+enum { OXY_SCHED_BATCHED = 0, OXY_SCHED_UNBATCHED = 1, OXY_SCHED_UPPER_BOUND = 2 };
+typedef struct {
+  int32_t k;             /* decode steps per request per frame (Alg. 1 input k), >= 1 */
+  int32_t denoise_steps; /* S; 0 = no action expert (then chunk must be 0 too) */
+  int32_t chunk;         /* action tokens per denoise step (H) */
+  int32_t max_active;    /* capacity of the active set R; 0 = unbounded.  An observation that
+                            arrives while R is full still gets its action, but no request */
+  int32_t mode;
+} oxy_sched_config;
+int32_t oxy_sched_create(oxy_pool *pool, const oxy_sched_config *cfg, oxy_sched **out);
+/* Releases every stream the scheduler still holds and the prefixes of an unfinished frame. */
+int32_t oxy_sched_destroy(oxy_sched *sched);
+/* One new observation whose prefill KV is prefix_id (appended by the caller, all layers); only
+ * before the first step of a frame.  target_len = N, the request's total decode length.
+ * *request_id = the new id, or -1 if the active set is full.  The scheduler takes over the
+ * creator's reference of the prefix and drops it at the end of the frame. */
+int32_t oxy_sched_admit(oxy_sched *sched, int32_t prefix_id, int32_t target_len,
+                        int32_t *request_id);
+/* The next step of the current frame: items HOST [cap] receives *n_items (stream, n_new) pairs
+ * ready for oxy_batch_build, of which the first *n_action_items (may be NULL) are action
+ * chunks.  *n_items = 0: the frame has no more steps.  A returned step counts as executed. */
+int32_t oxy_sched_next_step(oxy_sched *sched, oxy_item *items, int32_t cap, int32_t *n_items,
+                            int32_t *n_action_items);
+/* Only when the frame has no more steps.  Releases the frame's action streams, the finished
+ * requests (ascending id, written to finished HOST [cap]) and the frame's prefixes. */
+int32_t oxy_sched_end_frame(oxy_sched *sched, int32_t *finished, int32_t cap,
+                            int32_t *n_finished);
+int32_t oxy_sched_info(oxy_sched *sched, int32_t *frame, int32_t *n_active, int32_t *n_created,
+                       int32_t *n_rejected);
+/* OXY_ERR_BAD_ID if the request is not in the active set (any output may be NULL). */
+int32_t oxy_sched_request_info(oxy_sched *sched, int32_t request_id, int32_t *stream_id,
+                               int32_t *done, int32_t *target, int32_t *birth_frame);
+
 const char *oxy_last_error(void);
 int32_t oxy_version(void);
 

@@ -20,6 +20,7 @@ POOL_HOST_ONLY = 1
 BATCH_APPEND_ONLY = 1
 STEP_FUSE_ACROSS_LAYERS = 1
 STEP_FOLD_APPEND = 2
+SCHED_BATCHED, SCHED_UNBATCHED, SCHED_UPPER_BOUND = 0, 1, 2
 
 EXPORTS = [
     "oxy_version", "oxy_last_error", "oxy_kv_bytes", "oxy_workspace_bytes", "oxy_pool_create",
@@ -31,6 +32,8 @@ EXPORTS = [
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
     "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe", "oxy_read_probe",
+    "oxy_sched_create", "oxy_sched_destroy", "oxy_sched_admit", "oxy_sched_next_step",
+    "oxy_sched_end_frame", "oxy_sched_info", "oxy_sched_request_info",
 ]
 
 
@@ -53,6 +56,11 @@ class PoolConfig(ctypes.Structure):
         ("stream_split_tokens", ctypes.c_int32),
         ("flags", ctypes.c_int32),
     ]
+
+
+class SchedConfig(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_int32), ("denoise_steps", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("max_active", ctypes.c_int32), ("mode", ctypes.c_int32)]
 
 
 class Item(ctypes.Structure):
@@ -106,6 +114,13 @@ def lib():
             "oxy_batch_work": [vp, pi32, i32],
             "oxy_copy_probe": [vp, vp, ctypes.c_size_t, vp],
             "oxy_read_probe": [vp, ctypes.c_size_t, vp, vp],
+            "oxy_sched_create": [vp, ctypes.POINTER(SchedConfig), ctypes.POINTER(vp)],
+            "oxy_sched_destroy": [vp],
+            "oxy_sched_admit": [vp, i32, i32, pi32],
+            "oxy_sched_next_step": [vp, ctypes.POINTER(Item), i32, pi32, pi32],
+            "oxy_sched_end_frame": [vp, pi32, i32, pi32],
+            "oxy_sched_info": [vp, pi32, pi32, pi32, pi32],
+            "oxy_sched_request_info": [vp, i32, pi32, pi32, pi32, pi32],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -319,3 +334,50 @@ def oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream):
 
 def oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream):
     _check(lib().oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream or None))
+
+
+# ---- frame scheduler -------------------------------------------------------------------
+def oxy_sched_create(pool, k, denoise_steps, chunk, max_active=0, mode=SCHED_BATCHED):
+    cfg = SchedConfig(k, denoise_steps, chunk, max_active, mode)
+    out = ctypes.c_void_p()
+    _check(lib().oxy_sched_create(pool, ctypes.byref(cfg), ctypes.byref(out)))
+    return out
+
+
+def oxy_sched_destroy(sched):
+    _check(lib().oxy_sched_destroy(sched))
+
+
+def oxy_sched_admit(sched, prefix_id, target_len):
+    rid = _i32()
+    _check(lib().oxy_sched_admit(sched, prefix_id, target_len, ctypes.byref(rid)))
+    return rid.value
+
+
+def oxy_sched_next_step(sched, cap=4096):
+    """Returns (items, n_action_items); items == [] when the frame has no more steps."""
+    arr = (Item * cap)()
+    n, na = _i32(), _i32()
+    _check(lib().oxy_sched_next_step(sched, arr, cap, ctypes.byref(n), ctypes.byref(na)))
+    return [(arr[i].stream_id, arr[i].n_new) for i in range(n.value)], na.value
+
+
+def oxy_sched_end_frame(sched, cap=4096):
+    out = (ctypes.c_int32 * cap)()
+    n = _i32()
+    _check(lib().oxy_sched_end_frame(sched, out, cap, ctypes.byref(n)))
+    return list(out[:n.value])
+
+
+def oxy_sched_info(sched):
+    a, b, c, d = _i32(), _i32(), _i32(), _i32()
+    _check(lib().oxy_sched_info(sched, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                ctypes.byref(d)))
+    return a.value, b.value, c.value, d.value
+
+
+def oxy_sched_request_info(sched, request_id):
+    a, b, c, d = _i32(), _i32(), _i32(), _i32()
+    _check(lib().oxy_sched_request_info(sched, request_id, ctypes.byref(a), ctypes.byref(b),
+                                        ctypes.byref(c), ctypes.byref(d)))
+    return a.value, b.value, c.value, d.value

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboxy.so")
-SOURCES = ["oxy_kernels.hip", "oxy_pool.cpp"]
+SOURCES = ["oxy_kernels.hip", "oxy_pool.cpp", "oxy_sched.cpp"]
 # packed fp32 VALU forms are switched off for device code on purpose
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -166,6 +166,7 @@ char* layer_base(const oxy_pool* p, int32_t layer) {
 extern "C" {
 
 const char* oxy_last_error(void) { return g_err; }
+__attribute__((visibility("hidden"))) void oxy_internal_set_error(const char* msg) { snprintf(g_err, sizeof(g_err), "%s", msg); }
 int32_t oxy_version(void) { return 1; }
 
 size_t oxy_kv_bytes(const oxy_pool_config* cfg) {
