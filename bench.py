@@ -326,6 +326,82 @@ def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
     return out
 
 
+def _arrival_patterns(frames, seed=14371300):
+    """Arrival patterns of the paper's workload generalisation (Sec. 4.4): per frame the list
+    of total decode lengths N of the observations that arrive (seeded, synthetic)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    pats = {"one_per_frame": [[60]] * frames}
+    for r in (2, 4):
+        pats["uniform_%d" % r] = [[60] * r] * frames
+    for lam in (0.5, 1.0, 2.0):
+        pats["poisson_%g" % lam] = [[60] * int(rng.poisson(lam)) for _ in range(frames)]
+    for name, p_short in (("short1_long3", 0.25), ("short1_long1", 0.5), ("short3_long1", 0.75)):
+        pats["lengths_" + name] = [[20 if rng.random() < p_short else 100] for _ in range(frames)]
+    return pats
+
+
+def bench_arrivals(device, split_tokens, frames=24, warm=12, k=10, s_act=10, chunk=50,
+                   prefix_len=832):
+    """Attention-only version of the paper's arrival-pattern sweep and ablation (Sec. 4.3-4.4):
+    frames are driven by the library's scheduler; per pattern and variant the frame time, the
+    per-request action frequency 1/T, the mean decode batch and the totals per second.  The
+    prefill is represented by its KV write (prefix append) only; the host synchronises after
+    every step, as a decode loop that samples on the host would."""
+    import torch
+    from paper_2603_14371_amd import binding as B, synth
+    from paper_2603_14371_amd.harness import GpuWorld
+    nb, L = 8192, 18
+    w = synth._workload("arrivals", 14371300, L, nb, [])
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False,
+                  max_q_tokens=4 * chunk + 80, max_append_tokens=1024, max_partials=16384)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(5)
+    pk = torch.randn((L, 2, prefix_len, 256), device=device, generator=gen).to(torch.bfloat16)
+    runner = StepRunner(gw, 4 * chunk + 80, device, 6)
+    stream = runner.stream
+    out = {}
+    for pname, arrivals in _arrival_patterns(warm + frames).items():
+        res = {}
+        for mname, mode in (("batched", B.SCHED_BATCHED), ("unbatched", B.SCHED_UNBATCHED),
+                            ("upper_bound", B.SCHED_UPPER_BOUND)):
+            sched = B.oxy_sched_create(gw.pool, k, s_act, chunk, 64, mode)
+            t_frames, n_dec_items, n_dec_steps, n_obs = [], 0, 0, 0
+            for t, targets in enumerate(arrivals):
+                torch.cuda.synchronize(device)
+                t0 = time.perf_counter()
+                for n in targets:
+                    pid = B.oxy_prefix_create(gw.pool)
+                    for layer in range(L):
+                        B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(),
+                                            pk[layer, 1].data_ptr(), prefix_len, 0, stream)
+                    B.oxy_sched_admit(sched, pid, n)
+                while True:
+                    items, n_action = B.oxy_sched_next_step(sched)
+                    if not items:
+                        break
+                    runner.step(items)
+                    torch.cuda.synchronize(device)
+                    if t >= warm and len(items) > n_action:
+                        n_dec_items += len(items) - n_action
+                        n_dec_steps += 1
+                B.oxy_sched_end_frame(sched)
+                if t >= warm:
+                    t_frames.append(time.perf_counter() - t0)
+                    n_obs += len(targets)
+            B.oxy_sched_destroy(sched)
+            T = float(np.mean(t_frames))
+            res[mname] = {
+                "frame_ms": round(T * 1e3, 3),
+                "action_hz_per_request": round(1.0 / T, 1),
+                "avg_decode_batch": round(n_dec_items / max(1, n_dec_steps), 2),
+                "actions_per_s": round(n_obs * chunk / sum(t_frames), 1),
+                "decode_tokens_per_s": round(n_dec_items / sum(t_frames), 1),
+            }
+        out[pname] = res
+    gw.close()
+    return out
+
+
 def stream_probe(device, n_bytes, layers=18, reps=5):
     """What a plain read-only streaming kernel reaches on this machine for the same bytes per
     launch as one attention launch (cycling over `layers` distinct regions so that nothing sits
@@ -411,6 +487,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-frame", action="store_true")
     ap.add_argument("--no-cross-task", action="store_true")
+    ap.add_argument("--no-arrivals", action="store_true")
+    ap.add_argument("--only-arrivals", action="store_true",
+                    help="run only the arrival-pattern sweep (frames driven by the scheduler)")
     ap.add_argument("--no-alt-schedules", action="store_true",
                     help="profiling aid: skip the passes with the other launch schedules")
     ap.add_argument("--only-frame", action="store_true",
@@ -429,6 +508,9 @@ def main():
     device = torch.device("cuda:0")
     if args.only_frame:
         print(json.dumps({"pi05_frame": bench_frame(device, args.split_tokens)}))
+        return
+    if args.only_arrivals:
+        print(json.dumps({"arrival_patterns": bench_arrivals(device, args.split_tokens)}))
         return
     s = bench_stress(args, device)
     out = {
@@ -476,6 +558,8 @@ def main():
                              bench_cross_task(device, args.split_tokens).items()}
     if not args.no_frame:
         out["pi05_frame"] = {k: round(v, 2) for k, v in bench_frame(device, args.split_tokens).items()}
+    if not args.no_arrivals:
+        out["arrival_patterns"] = bench_arrivals(device, args.split_tokens)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
