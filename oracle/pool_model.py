@@ -26,6 +26,11 @@ refcounts are compared bit for bit):
 * An ACTION item is rewound to length 0 at every batch build (its chunk K/V is
   transient per denoising step and reuses the same blocks); a DECODE item grows.
 * A failing call changes nothing (NO_BLOCKS is detected before any pop).
+* Fork (an extension beyond the paper, for prefixes of consecutive frames that begin with
+  the same history segment): the child prefix starts with the parent's first n tokens, n a
+  multiple of the page size, by listing the parent's blocks (refcount + 1 each); the shared
+  range becomes read-only in both (an append below it fails with SEALED); the child appends
+  behind it into blocks of its own.  Release treats shared blocks like any other entry.
 """
 
 ACTION = 0
@@ -51,6 +56,7 @@ class _Prefix:
         self.sealed = False
         self.handle = True      # creator's reference still held
         self.n_streams = 0
+        self.frozen = 0         # tokens below this position are shared with a fork
 
 
 class _Stream:
@@ -110,7 +116,7 @@ class PoolModel:
             raise PoolError(ERR_BAD_ID)
         if not (0 <= layer < self.n_layers) or n_tokens < 1 or pos0 < 0 or pos0 > p.length:
             raise PoolError(ERR_INVALID_ARG)
-        if p.sealed:
+        if p.sealed or pos0 < p.frozen:
             raise PoolError(ERR_SEALED)
         need = self._blocks_for(pos0 + n_tokens) - len(p.blocks)
         if need > len(self.free):
@@ -120,6 +126,24 @@ class PoolModel:
         p.length = max(p.length, pos0 + n_tokens)
         return [p.blocks[t // self.page] * self.page + t % self.page
                 for t in range(pos0, pos0 + n_tokens)]
+
+    def prefix_fork(self, parent_id, n_tokens):
+        """New prefix whose tokens 0 .. n_tokens-1 are the parent's (same blocks)."""
+        p = self.prefixes.get(parent_id)
+        if p is None:
+            raise PoolError(ERR_BAD_ID)
+        if n_tokens < 0 or n_tokens % self.page != 0 or n_tokens > p.length:
+            raise PoolError(ERR_INVALID_ARG)
+        pid = self.next_prefix_id
+        self.next_prefix_id += 1
+        c = _Prefix()
+        c.blocks = p.blocks[:n_tokens // self.page]
+        for b in c.blocks:
+            self.ref[b] += 1
+        c.length = c.frozen = n_tokens
+        p.frozen = max(p.frozen, n_tokens)
+        self.prefixes[pid] = c
+        return pid
 
     def prefix_release(self, pid):
         p = self.prefixes.get(pid)

@@ -5,6 +5,7 @@ A trace is a list of plain dicts (no code of either implementation inside):
 
   {"op": "prefix_create", "pid": expected id}
   {"op": "prefix_append", "pid", "n", "pos0", "data": recipe}       every layer gets its own data
+  {"op": "prefix_fork", "parent", "n", "pid": expected id}          child starts as parent[:n]
   {"op": "stream_create", "pid" (-1 = none), "kind", "sid": expected id}
   {"op": "stream_rewind", "sid", "len"}
   {"op": "step", "items": [(sid, n_new), ...], "data": recipe, "attend": bool}
@@ -59,6 +60,11 @@ class OracleWorld:
                 self.prefix_kv[pid][layer] = (
                     np.concatenate([old[0][:pos0], k]), np.concatenate([old[1][:pos0], v]))
             return {"slots": slots}
+        if kind == "prefix_fork":
+            pid = self.pool.prefix_fork(op["parent"], op["n"])
+            self.prefix_kv[pid] = {layer: (k[:op["n"]].copy(), v[:op["n"]].copy())
+                                   for layer, (k, v) in self.prefix_kv[op["parent"]].items()}
+            return {"pid": pid}
         if kind == "stream_create":
             sid = self.pool.stream_create(op["pid"], op["kind"])
             self.stream_kv[sid] = {}

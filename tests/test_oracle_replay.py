@@ -129,3 +129,36 @@ def test_outputs_do_not_depend_on_block_placement_but_tables_do():
     assert np.array_equal(r1[-1]["O"][0], r2[-1]["O"][0])
     assert r1[-1]["slots"] != r2[-1]["slots"]
     assert r1[-1]["O"][0].shape == (11, 8, 32)
+
+
+def test_forked_prefix_reads_like_an_unforked_copy():
+    """A child prefix that shares its first 32 tokens with its parent and continues with 20
+    tokens of its own gives every query exactly what a prefix holding the same 52 tokens in
+    blocks of its own gives; only the block tables differ."""
+    from oracle.pool_model import ACTION, DECODE
+    src = synth.DataSource(777)
+    hist = {"tag": 1, "tok0": 0, "n_total": 48}
+    tail = {"tag": 2, "tok0": 0, "n_total": 20}
+    step = {"op": "step", "items": [(0, 6), (1, 1)], "attend": True,
+            "data": {"tag": 3, "tok0": 0, "n_total": 7}}
+    forked = [{"op": "prefix_create", "pid": 0},
+              {"op": "prefix_append", "pid": 0, "n": 48, "pos0": 0, "data": hist},
+              {"op": "prefix_fork", "parent": 0, "n": 32, "pid": 1},
+              {"op": "prefix_append", "pid": 1, "n": 20, "pos0": 32, "data": tail},
+              {"op": "stream_create", "pid": 1, "kind": ACTION, "sid": 0},
+              {"op": "stream_create", "pid": 1, "kind": DECODE, "sid": 1}, step]
+    plain = [{"op": "prefix_create", "pid": 0},
+             {"op": "prefix_append", "pid": 0, "n": 32, "pos0": 0, "data": hist},
+             {"op": "prefix_append", "pid": 0, "n": 20, "pos0": 32, "data": tail},
+             {"op": "stream_create", "pid": 0, "kind": ACTION, "sid": 0},
+             {"op": "stream_create", "pid": 0, "kind": DECODE, "sid": 1}, step]
+    outs = []
+    for trace in (forked, plain):
+        ow = OracleWorld(32, 1, src, 0.0625)
+        res = [ow.apply(op) for op in trace]
+        outs.append(res[-1])
+        if trace is forked:
+            assert ow.pool.prefixes[1].blocks[:2] == ow.pool.prefixes[0].blocks[:2]
+            assert ow.pool.ref[ow.pool.prefixes[0].blocks[0]] == 4   # two handles, two streams
+    assert np.array_equal(outs[0]["O"][0], outs[1]["O"][0])
+    assert np.array_equal(outs[0]["LSE"][0], outs[1]["LSE"][0])

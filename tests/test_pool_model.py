@@ -64,6 +64,41 @@ def test_failure_is_atomic():
     assert e.value.code == ERR_NO_BLOCKS and m.prefixes[p].blocks == []
 
 
+def test_hand_worked_fork():
+    """Fork worked by hand: the child lists the parent's first blocks, both freeze the shared
+    range, the child grows into blocks of its own, and blocks return when the last table that
+    lists them goes."""
+    m = PoolModel(8, page_size=4)                     # free stack pops 0, 1, 2, ...
+    p = m.prefix_create()
+    m.prefix_append(p, 0, 10, 0)                      # blocks 0, 1, 2
+    for bad in (3, 12, -4):                           # not a page multiple / beyond the parent
+        with pytest.raises(PoolError) as e:
+            m.prefix_fork(p, bad)
+        assert e.value.code == ERR_INVALID_ARG
+    with pytest.raises(PoolError) as e:
+        m.prefix_fork(7, 4)
+    assert e.value.code == ERR_BAD_ID
+    c = m.prefix_fork(p, 8)
+    assert c == 1 and m.prefixes[c].blocks == [0, 1] and m.prefixes[c].length == 8
+    assert m.ref[:3] == [2, 2, 1]
+    assert m.prefix_append(c, 0, 5, 8) == [12, 13, 14, 15, 16]    # own blocks 3, 4
+    for pid, pos in ((c, 4), (p, 7)):                 # the shared range is read-only in both
+        with pytest.raises(PoolError) as e:
+            m.prefix_append(pid, 0, 1, pos)
+        assert e.value.code == ERR_SEALED
+    assert m.prefix_append(p, 0, 2, 8) == [8, 9]      # the parent's unshared tail is still its own
+    d = m.stream_create(c, DECODE)
+    assert m.ref[:5] == [3, 3, 1, 2, 2]
+    m.prefix_release(p)                               # block 2 returns, 0 and 1 live on in the child
+    assert m.free[-1] == 2 and m.ref[:3] == [2, 2, 0] and p not in m.prefixes
+    m.prefix_release(c)
+    m.stream_release(d)
+    assert m.free[-4:] == [0, 1, 3, 4] and m.stats() == (8, 0, 0)
+    e0 = m.prefix_create()
+    z = m.prefix_fork(e0, 0)                          # an empty fork is an empty prefix
+    assert m.prefixes[z].blocks == [] and m.prefix_append(z, 0, 1, 0) == [16]
+
+
 def _check_conservation(m):
     """free + distinct live blocks = all; ref[b] = number of tables holding b (+ handle)."""
     count = [0] * m.num_blocks
@@ -91,6 +126,13 @@ def test_conservation_under_random_operations(seed):
                 pid = m.prefix_create()
                 open_prefixes.append(pid)
                 m.prefix_append(pid, 0, int(rng.integers(1, 20)), 0)
+            elif r < 0.16 and m.prefixes:
+                parent = int(rng.choice(list(m.prefixes)))
+                n = 4 * int(rng.integers(0, m.prefixes[parent].length // 4 + 1))
+                pid = m.prefix_fork(parent, n)
+                open_prefixes.append(pid)
+                if rng.random() < 0.7:
+                    m.prefix_append(pid, 0, int(rng.integers(1, 12)), n)
             elif r < 0.3:
                 pid = int(rng.choice(open_prefixes)) if open_prefixes and rng.random() < 0.8 else -1
                 m.stream_create(pid, int(rng.integers(0, 2)))
