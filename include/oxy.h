@@ -142,6 +142,16 @@ int32_t oxy_prefix_create(oxy_pool *pool, int32_t *prefix_id); /* holds the crea
  * reached (by whichever layer comes first).  SEALED once a stream is attached. */
 int32_t oxy_prefix_append(oxy_pool *pool, int32_t prefix_id, int32_t layer, const void *k,
                           const void *v, int32_t n_tokens, int32_t pos0, void *hip_stream);
+/* Fork (an extension for observations of consecutive frames that begin with the same history
+ * segment): *prefix_id is a new prefix whose tokens 0..n_tokens-1 ARE the parent's — it lists the
+ * parent's first n_tokens/16 blocks (refcount + 1 each, no copy).  n_tokens must be a multiple of
+ * the page size and at most the parent's length; the caller must have appended that range in
+ * every layer.  The shared range becomes read-only in parent and child (append below it:
+ * OXY_ERR_SEALED); the child continues with oxy_prefix_append at pos0 >= n_tokens into blocks of
+ * its own.  The parent may be any prefix that still exists, also one whose creator's reference
+ * is gone but that requests keep alive. */
+int32_t oxy_prefix_fork(oxy_pool *pool, int32_t parent_prefix_id, int32_t n_tokens,
+                        int32_t *prefix_id);
 /* Drops the creator's reference; attached streams keep the blocks alive (a request carried
  * over to later frames keeps the prefill cache of its birth frame, Sec. 3.2). */
 int32_t oxy_prefix_release(oxy_pool *pool, int32_t prefix_id);

@@ -39,6 +39,7 @@ struct Prefix {
   bool sealed = false;
   bool handle = true;  // creator's reference still held
   int32_t n_streams = 0;
+  int32_t frozen = 0;  // tokens below this position are shared with a fork: read-only
 };
 
 struct Stream {
@@ -287,6 +288,9 @@ int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k
                 n_tokens, pos0, px.len);
   if (!p->host_only && (!k || !v)) return fail(OXY_ERR_INVALID_ARG, "prefix_append: null k/v");
   if (px.sealed) return fail(OXY_ERR_SEALED, "prefix_append: prefix %d has streams attached", pid);
+  if (pos0 < px.frozen)
+    return fail(OXY_ERR_SEALED, "prefix_append: tokens below %d of prefix %d are shared with a fork",
+                px.frozen, pid);
   int32_t need = blocks_for(pos0 + n_tokens) - (int32_t)px.blocks.size();
   if (need > (int32_t)p->free_stack.size())
     return fail(OXY_ERR_NO_BLOCKS, "prefix_append: need %d blocks, %zu free", need,
@@ -318,6 +322,24 @@ int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k
     if (e != hipSuccess) return hip_fail(e, "prefix_append: launch");
     done += n;
   }
+  return OXY_OK;
+}
+
+int32_t oxy_prefix_fork(oxy_pool* p, int32_t parent_id, int32_t n_tokens, int32_t* prefix_id) {
+  if (!p || !prefix_id) return fail(OXY_ERR_INVALID_ARG, "prefix_fork: null argument");
+  auto it = p->prefixes.find(parent_id);
+  if (it == p->prefixes.end()) return fail(OXY_ERR_BAD_ID, "prefix_fork: no prefix %d", parent_id);
+  if (n_tokens < 0 || n_tokens % kPage != 0 || n_tokens > it->second.len)
+    return fail(OXY_ERR_INVALID_ARG, "prefix_fork: %d tokens of prefix %d (len %d, page %d)", n_tokens,
+                parent_id, it->second.len, kPage);
+  Prefix child;
+  child.blocks.assign(it->second.blocks.begin(), it->second.blocks.begin() + n_tokens / kPage);
+  child.len = child.frozen = n_tokens;
+  it->second.frozen = std::max(it->second.frozen, n_tokens);
+  for (int32_t b : child.blocks) p->ref[b]++;
+  int32_t id = p->next_prefix++;
+  p->prefixes.emplace(id, std::move(child));   // may rehash: `it` is not used after this
+  *prefix_id = id;
   return OXY_OK;
 }
 

@@ -94,6 +94,8 @@ class GpuWorld:
             blocks = B.oxy_prefix_blocks(self.pool, op["pid"])
             return {"slots": [blocks[t // 16] * 16 + t % 16
                               for t in range(op["pos0"], op["pos0"] + op["n"])]}
+        if kind == "prefix_fork":
+            return {"pid": B.oxy_prefix_fork(self.pool, op["parent"], op["n"])}
         if kind == "stream_create":
             sid = B.oxy_stream_create(self.pool, op["pid"], op["kind"])
             self.kinds[sid] = op["kind"]

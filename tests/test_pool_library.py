@@ -52,17 +52,27 @@ def test_random_operation_sequences_match_the_model(seed):
     pool = _host_pool(nb, free_order=order, max_q_tokens=256)
     model = PoolModel(nb, 16, 2, order.tolist())
     prefixes, n_checked = [], 0
-    for _ in range(500):
+    for _ in range(800):
         r = rng.random()
         if r < 0.1:
             a, b = _both(pool, model, lambda: B.oxy_prefix_create(pool), model.prefix_create)
             assert a == b
             prefixes.append(a)
+        elif r < 0.14 and prefixes:
+            parent = int(rng.choice(prefixes + [98]))
+            plen = model.prefixes[parent].length if parent in model.prefixes else 0
+            n = int(rng.choice([0, 16 * int(rng.integers(0, plen // 16 + 1)), plen, plen + 16, 8]))
+            a, b = _both(pool, model, lambda: B.oxy_prefix_fork(pool, parent, n),
+                         lambda: model.prefix_fork(parent, n))
+            assert a == b
+            if a is not None:
+                prefixes.append(a)
         elif r < 0.25 and prefixes:
             pid = int(rng.choice(prefixes + [99]))
             n, layer = int(rng.integers(0, 70)), int(rng.integers(0, 3))
             plen = model.prefixes[pid].length if pid in model.prefixes else 0
-            pos0 = int(rng.choice([0, plen, plen + 1]))
+            frozen = model.prefixes[pid].frozen if pid in model.prefixes else 0
+            pos0 = int(rng.choice([0, plen, plen + 1, frozen]))
             _both(pool, model, lambda: B.oxy_prefix_append(pool, pid, layer, 0, 0, n, pos0, 0),
                   lambda: model.prefix_append(pid, layer, n, pos0))
         elif r < 0.4:
