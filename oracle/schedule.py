@@ -27,6 +27,12 @@ to completion before the next one starts, so nothing carries over; "upper_bound"
 the single-frame decoding oracle of the ablation: k tokens are decoded and the rest
 of the request is dropped at frame end.
 
+Budget calibration (Sec. 3.2: k is chosen offline from the target frame rate and the hardware
+so that batched decoding over the typical active batch fits into what remains of the frame
+after action denoising): `steady_frame_time` prices the steps of a steady-state frame, found
+by running the simulation until it is periodic, with measured per-step costs; `calibrate_k`
+is the definition itself, the largest k whose steady-state frame still meets the rate.
+
 What pins it (tests/test_oracle_schedule.py): the worked example of Fig. 3 (N = 12,
 k = 4 -> three requests in parallel, four tokens each per frame), the rule B = N / k
 of Sec. 4.2 and its extension r N / k for r arrivals per frame, token conservation
@@ -113,3 +119,27 @@ def simulate(arrivals, k, denoise_steps, mode=BATCHED, max_active=0):
 def decode_batch_sizes(frames):
     """Number of requests decoding in each step that decodes at all, per frame."""
     return [[len(dec) for _, dec in f["steps"] if dec] for f in frames]
+
+
+def steady_frame_time(k, denoise_steps, target, arrivals_per_frame, t_obs, t_mixed, t_decode):
+    """Time of one frame once the schedule has become periodic: every arriving observation
+    costs t_obs (its prefill stand-in and fan-out), a step that denoises costs t_mixed[b] and a
+    decode-only step t_decode[b], b = number of requests decoding in that step."""
+    lifetime = -(-target // k)
+    frames = simulate([[target] * arrivals_per_frame] * (lifetime + 2), k, denoise_steps)
+    total = arrivals_per_frame * t_obs
+    for act, dec in frames[-1]["steps"]:
+        total += t_mixed[len(dec)] if act else t_decode[len(dec)]
+    return total
+
+
+def calibrate_k(denoise_steps, target, arrivals_per_frame, t_obs, t_mixed, t_decode, target_hz):
+    """Largest per-frame budget k in 1..target whose steady-state frame time stays within
+    1 / target_hz; 0 if there is none.  Returns (k, frame time at that k)."""
+    best = (0, 0.0)
+    for k in range(1, target + 1):
+        t = steady_frame_time(k, denoise_steps, target, arrivals_per_frame, t_obs, t_mixed,
+                              t_decode)
+        if t <= 1.0 / target_hz:
+            best = (k, t)
+    return best

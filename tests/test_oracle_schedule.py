@@ -112,3 +112,37 @@ def test_full_active_set_serves_the_action_only():
     assert [f["admitted"] for f in frames[:5]] == [[0], [1], [2], [-1], [-1]]
     assert all(len(dec) <= 3 for f in frames for _, dec in f["steps"])
     assert all(sum(1 for act, _ in f["steps"] if act) == 2 for f in frames)
+
+
+def test_steady_frame_time_of_the_worked_example_by_hand():
+    """Fig. 3 shape (N = 12, k = 4, one arrival per frame) with S = 2: the steady frame has two
+    mixed steps and two decode-only steps, each with three requests decoding."""
+    t_mixed = [10.0, 11.0, 12.0, 13.0, 14.0]
+    t_dec = [0.0, 3.0, 3.5, 4.0, 4.5]
+    t = S.steady_frame_time(4, 2, 12, 1, t_obs=20.0, t_mixed=t_mixed, t_decode=t_dec)
+    assert t == 20.0 + 2 * 13.0 + 2 * 4.0
+    # N not a multiple of k: N = 10, k = 4 -> ages 0, 1 decode 4 tokens, age 2 decodes 2
+    t = S.steady_frame_time(4, 2, 10, 1, 20.0, t_mixed, t_dec)
+    assert t == 20.0 + 2 * 13.0 + 2 * 3.5
+    # budget below S: the denoise steps beyond k carry no decoding
+    t = S.steady_frame_time(1, 3, 3, 1, 20.0, t_mixed, t_dec)
+    assert t == 20.0 + 13.0 + 2 * 10.0
+
+
+def test_calibrated_budget_is_the_largest_that_meets_the_rate():
+    n = 24
+    t_mixed = [100.0 + 2.0 * b for b in range(2 * n + 1)]
+    t_dec = [40.0 + 2.0 * b for b in range(2 * n + 1)]
+    # closed form for k | N, one arrival per frame, k >= S: T = t_obs + S t_mixed[N/k] + (k-S) t_dec[N/k]
+    s_act, t_obs = 4, 200.0
+    for k in (4, 6, 8, 12, 24):
+        b = n // k
+        want = t_obs + s_act * t_mixed[b] + (k - s_act) * t_dec[b]
+        assert S.steady_frame_time(k, s_act, n, 1, t_obs, t_mixed, t_dec) == want
+    budget_us = 1000.0
+    k, t = S.calibrate_k(s_act, n, 1, t_obs, t_mixed, t_dec, 1.0 / budget_us)
+    assert 1 <= k < n and t <= budget_us
+    for bigger in range(k + 1, n + 1):
+        assert S.steady_frame_time(bigger, s_act, n, 1, t_obs, t_mixed, t_dec) > budget_us
+    assert S.calibrate_k(s_act, n, 1, t_obs, t_mixed, t_dec, 1.0 / 100.0) == (0, 0.0)
+    assert S.calibrate_k(s_act, n, 1, t_obs, t_mixed, t_dec, 1.0 / 1e9)[0] == n
