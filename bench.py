@@ -402,6 +402,110 @@ def bench_arrivals(device, split_tokens, frames=24, warm=12, k=10, s_act=10, chu
     return out
 
 
+def bench_calibration(device, split_tokens, targets_hz=(350.0, 300.0, 250.0), n_len=60, s_act=10,
+                      chunk=50, prefix_len=832, reps=12):
+    """Attention-only version of the offline calibration of the per-frame budget k (Sec. 3.2):
+    measure the cost of a mixed step and of a decode-only step for every decode batch size,
+    let the library pick the largest k whose steady-state frame meets a target frame rate, then
+    run scheduler-driven frames with that k and report the measured frame time beside the
+    modelled one."""
+    import torch
+    from paper_2603_14371_amd import binding as B, synth
+    from paper_2603_14371_amd.harness import GpuWorld
+    nb, L, bmax = 8192, 18, n_len
+    w = synth._workload("calibration", 14371400, L, nb, [])
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False,
+                  max_q_tokens=chunk + bmax + 8, max_append_tokens=1024, max_partials=16384)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(9)
+    pk = torch.randn((L, 2, prefix_len, 256), device=device, generator=gen).to(torch.bfloat16)
+    runner = StepRunner(gw, chunk + bmax + 8, device, 10)
+    stream = runner.stream
+
+    def new_prefix():
+        pid = B.oxy_prefix_create(gw.pool)
+        for layer in range(L):
+            B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(), pk[layer, 1].data_ptr(),
+                                prefix_len, 0, stream)
+        return pid
+
+    def timed(items):
+        ts = []
+        for i in range(reps + 3):
+            torch.cuda.synchronize(device)
+            t0 = time.perf_counter()
+            runner.step(items)
+            torch.cuda.synchronize(device)
+            if i >= 3:
+                ts.append(time.perf_counter() - t0)
+        return float(np.median(ts)) * 1e6
+
+    # cost tables: one action chunk on a fresh observation + b requests in mid-life, each on the
+    # prefix of its own birth frame
+    act_pid = new_prefix()
+    act = B.oxy_stream_create(gw.pool, act_pid, B.KIND_ACTION)
+    dec = []
+    t_mixed, t_dec = [timed([(act, chunk)])], [0.0]
+    for b in range(1, bmax + 1):
+        sid = B.oxy_stream_create(gw.pool, new_prefix(), B.KIND_DECODE)
+        batch = B.oxy_batch_build(gw.pool, [(sid, n_len // 2)], B.BATCH_APPEND_ONLY, stream)
+        B.oxy_batch_destroy(batch)      # history of half a request (contents do not matter)
+        dec.append(sid)
+        if b <= 12 or b % 6 == 0 or b == bmax:
+            t_mixed.append(timed([(act, chunk)] + [(s_, 1) for s_ in dec]))
+            t_dec.append(timed([(s_, 1) for s_ in dec]))
+        else:
+            t_mixed.append(None)
+            t_dec.append(None)
+    for tab in (t_mixed, t_dec):        # batch sizes not measured: linear between neighbours
+        known = [i for i, v in enumerate(tab) if v is not None]
+        for i, v in enumerate(tab):
+            if v is None:
+                lo = max(j for j in known if j < i)
+                hi = min(j for j in known if j > i)
+                tab[i] = tab[lo] + (tab[hi] - tab[lo]) * (i - lo) / (hi - lo)
+    torch.cuda.synchronize(device)
+    t0 = time.perf_counter()
+    for _ in range(5):
+        pid = new_prefix()
+    torch.cuda.synchronize(device)
+    t_obs = (time.perf_counter() - t0) / 5 * 1e6
+    B.oxy_stream_release(gw.pool, act)
+    for sid in dec:
+        B.oxy_stream_release(gw.pool, sid)
+    out = {"t_observation_us": round(t_obs, 1),
+           "t_mixed_us": {str(b): round(t_mixed[b], 1) for b in (0, 1, 2, 4, 6, 12, bmax)},
+           "t_decode_us": {str(b): round(t_dec[b], 1) for b in (1, 2, 4, 6, 12, bmax)},
+           "targets": []}
+    for hz in targets_hz:
+        k, model_us = B.oxy_sched_calibrate(t_mixed, t_dec, t_obs, s_act, n_len, 1, 1e6 / hz)
+        rec = {"target_hz": hz, "k": k, "modelled_frame_us": round(model_us, 1)}
+        if k > 0:
+            sched = B.oxy_sched_create(gw.pool, k, s_act, chunk, 0, B.SCHED_BATCHED)
+            warm = -(-n_len // k) + 2
+            ts = []
+            for t in range(warm + 16):
+                torch.cuda.synchronize(device)
+                f0 = time.perf_counter()
+                B.oxy_sched_admit(sched, new_prefix(), n_len)
+                while True:
+                    items, _ = B.oxy_sched_next_step(sched)
+                    if not items:
+                        break
+                    runner.step(items)
+                    torch.cuda.synchronize(device)
+                B.oxy_sched_end_frame(sched)
+                if t >= warm:
+                    ts.append(time.perf_counter() - f0)
+            B.oxy_sched_destroy(sched)
+            rec["measured_frame_us"] = round(float(np.mean(ts)) * 1e6, 1)
+            rec["measured_hz"] = round(1.0 / float(np.mean(ts)), 1)
+            rec["decode_tokens_per_s"] = round(n_len / float(np.mean(ts)), 1)
+        out["targets"].append(rec)
+    gw.close()
+    return out
+
+
 def stream_probe(device, n_bytes, layers=18, reps=5):
     """What a plain read-only streaming kernel reaches on this machine for the same bytes per
     launch as one attention launch (cycling over `layers` distinct regions so that nothing sits
@@ -510,7 +614,8 @@ def main():
         print(json.dumps({"pi05_frame": bench_frame(device, args.split_tokens)}))
         return
     if args.only_arrivals:
-        print(json.dumps({"arrival_patterns": bench_arrivals(device, args.split_tokens)}))
+        print(json.dumps({"arrival_patterns": bench_arrivals(device, args.split_tokens),
+                          "budget_calibration": bench_calibration(device, args.split_tokens)}))
         return
     s = bench_stress(args, device)
     out = {
@@ -560,6 +665,7 @@ def main():
         out["pi05_frame"] = {k: round(v, 2) for k, v in bench_frame(device, args.split_tokens).items()}
     if not args.no_arrivals:
         out["arrival_patterns"] = bench_arrivals(device, args.split_tokens)
+        out["budget_calibration"] = bench_calibration(device, args.split_tokens)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

@@ -291,6 +291,18 @@ int32_t oxy_sched_next_step(oxy_sched *sched, oxy_item *items, int32_t cap, int3
  * requests (ascending id, written to finished HOST [cap]) and the frame's prefixes. */
 int32_t oxy_sched_end_frame(oxy_sched *sched, int32_t *finished, int32_t cap,
                             int32_t *n_finished);
+/* Offline calibration of the per-frame budget k (Sec. 3.2): the largest k in 1..target_len whose
+ * steady-state frame, with arrivals_per_frame observations arriving in every frame, fits into
+ * frame_budget (= 1 / target frame rate).  The caller measures the costs, all in one unit of
+ * time: t_observation per arriving observation (prefill and fan-out), t_mixed[b] for a step
+ * that denoises while b requests decode, t_decode[b] for a decode-only step with b requests
+ * (HOST arrays of n_table entries, index b; t_decode[0] is never read).  *k_out = 0 if no k
+ * meets the budget; *frame_time_out (may be NULL) = the modelled frame time at *k_out.
+ * OXY_ERR_INVALID_ARG if a batch size that occurs is not covered by the tables. */
+int32_t oxy_sched_calibrate(const double *t_mixed, const double *t_decode, int32_t n_table,
+                            double t_observation, int32_t denoise_steps, int32_t target_len,
+                            int32_t arrivals_per_frame, double frame_budget, int32_t *k_out,
+                            double *frame_time_out);
 int32_t oxy_sched_info(oxy_sched *sched, int32_t *frame, int32_t *n_active, int32_t *n_created,
                        int32_t *n_rejected);
 /* OXY_ERR_BAD_ID if the request is not in the active set (any output may be NULL). */

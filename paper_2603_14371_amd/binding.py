@@ -34,7 +34,7 @@ EXPORTS = [
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
     "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe", "oxy_read_probe",
     "oxy_sched_create", "oxy_sched_destroy", "oxy_sched_admit", "oxy_sched_next_step",
-    "oxy_sched_end_frame", "oxy_sched_info", "oxy_sched_request_info",
+    "oxy_sched_end_frame", "oxy_sched_info", "oxy_sched_request_info", "oxy_sched_calibrate",
 ]
 
 
@@ -123,6 +123,9 @@ def lib():
             "oxy_sched_end_frame": [vp, pi32, i32, pi32],
             "oxy_sched_info": [vp, pi32, pi32, pi32, pi32],
             "oxy_sched_request_info": [vp, i32, pi32, pi32, pi32, pi32],
+            "oxy_sched_calibrate": [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                    i32, ctypes.c_double, i32, i32, i32, ctypes.c_double, pi32,
+                                    ctypes.POINTER(ctypes.c_double)],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -389,3 +392,17 @@ def oxy_sched_request_info(sched, request_id):
     _check(lib().oxy_sched_request_info(sched, request_id, ctypes.byref(a), ctypes.byref(b),
                                         ctypes.byref(c), ctypes.byref(d)))
     return a.value, b.value, c.value, d.value
+
+
+def oxy_sched_calibrate(t_mixed, t_decode, t_observation, denoise_steps, target_len,
+                        arrivals_per_frame, frame_budget):
+    """Returns (k, modelled frame time at k); k == 0 if no budget meets frame_budget."""
+    n = len(t_mixed)
+    assert len(t_decode) == n
+    a = (ctypes.c_double * n)(*t_mixed)
+    b = (ctypes.c_double * n)(*t_decode)
+    k, t = _i32(), ctypes.c_double(0.0)
+    _check(lib().oxy_sched_calibrate(a, b, n, t_observation, denoise_steps, target_len,
+                                     arrivals_per_frame, frame_budget, ctypes.byref(k),
+                                     ctypes.byref(t)))
+    return k.value, t.value

@@ -218,6 +218,40 @@ int32_t oxy_sched_end_frame(oxy_sched* s, int32_t* finished, int32_t cap, int32_
   return OXY_OK;
 }
 
+int32_t oxy_sched_calibrate(const double* t_mixed, const double* t_decode, int32_t n_table,
+                            double t_observation, int32_t denoise_steps, int32_t target_len,
+                            int32_t arrivals_per_frame, double frame_budget, int32_t* k_out,
+                            double* frame_time_out) {
+  if (!t_mixed || !t_decode || !k_out || n_table < 1 || denoise_steps < 0 || target_len < 1 ||
+      arrivals_per_frame < 1 || !(frame_budget > 0.0))
+    return fail(OXY_ERR_INVALID_ARG, "sched_calibrate: null or non-positive argument");
+  // Steady state under budget k with r arrivals per frame: a request lives ceil(N/k) frames, so
+  // at step s of a frame r * (floor(N/k) + [s < N mod k]) requests decode (s < k), and the
+  // frame has max(S, steps that decode) steps.
+  int32_t best_k = 0;
+  double best_t = 0.0;
+  for (int32_t k = 1; k <= target_len; ++k) {
+    const int32_t full = target_len / k, rem = target_len % k;
+    const int32_t n_dec_steps = full > 0 ? k : rem;
+    const int32_t n_steps = std::max(denoise_steps, n_dec_steps);
+    double t = arrivals_per_frame * t_observation;
+    for (int32_t s = 0; s < n_steps; ++s) {
+      const int64_t b = s < n_dec_steps ? (int64_t)arrivals_per_frame * (full + (s < rem ? 1 : 0)) : 0;
+      if (b >= n_table)
+        return fail(OXY_ERR_INVALID_ARG, "sched_calibrate: batch %lld at k = %d is beyond the cost tables (%d)",
+                    (long long)b, k, n_table);
+      t += s < denoise_steps ? t_mixed[b] : t_decode[b];
+    }
+    if (t <= frame_budget) {
+      best_k = k;
+      best_t = t;
+    }
+  }
+  *k_out = best_k;
+  if (frame_time_out) *frame_time_out = best_t;
+  return OXY_OK;
+}
+
 int32_t oxy_sched_info(oxy_sched* s, int32_t* frame, int32_t* n_active, int32_t* n_created,
                        int32_t* n_rejected) {
   if (!s) return fail(OXY_ERR_INVALID_ARG, "sched_info: null");

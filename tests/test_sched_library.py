@@ -132,3 +132,23 @@ def test_scheduler_argument_errors():
     B.oxy_sched_destroy(sched)
     assert B.oxy_pool_stats(pool) == (64, 0, 0)
     B.oxy_pool_destroy(pool)
+
+
+def test_calibrated_budget_matches_the_oracle():
+    """The library's closed form of the steady-state frame against the oracle's simulation."""
+    from oracle import schedule as S
+    rng = np.random.default_rng(3)
+    for _ in range(40):
+        n, r, s_act = int(rng.integers(1, 40)), int(rng.integers(1, 4)), int(rng.integers(0, 8))
+        size = r * n + 1
+        t_mixed = np.sort(rng.uniform(50, 400, size)).tolist()
+        t_dec = np.sort(rng.uniform(10, 200, size)).tolist()
+        t_obs = float(rng.uniform(0, 300))
+        budget = float(rng.uniform(200, 6000))
+        want = S.calibrate_k(s_act, n, r, t_obs, t_mixed, t_dec, 1.0 / budget)
+        got = B.oxy_sched_calibrate(t_mixed, t_dec, t_obs, s_act, n, r, budget)
+        assert got[0] == want[0] and abs(got[1] - want[1]) <= 1e-9 * max(1.0, want[1])
+    with pytest.raises(B.OxyError):       # batch sizes beyond the measured tables
+        B.oxy_sched_calibrate([1.0, 2.0], [1.0, 2.0], 0.0, 2, 12, 1, 100.0)
+    with pytest.raises(B.OxyError):
+        B.oxy_sched_calibrate([1.0], [1.0], 0.0, 2, 0, 1, 100.0)
