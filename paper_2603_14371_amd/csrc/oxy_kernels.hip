@@ -232,6 +232,9 @@ constexpr int kSmemBytes = 4 * 16 * kMergeStride * 4; // 66560 >= 2 * kStageByte
 static_assert(2 * kStageBytes <= kSmemBytes, "two stages must fit");
 constexpr float kGrow = 8.f;  // the reference max only moves when a logit exceeds it by 2^8
 
+// Timeline probes, compiled in only with -DOXY_DEBUG_PROBES (never in the shipped library):
+// thread 0 of every workgroup leaves wall-clock marks at fixed points of its path, plus its
+// path, step count, XCD and hardware id; oxy_debug_read copies them out.
 #ifdef OXY_DEBUG_PROBES
 __device__ unsigned long long g_dbg[16384 * 16];
 #define DBG_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) g_dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)

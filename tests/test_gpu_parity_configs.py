@@ -11,9 +11,10 @@ from parity_util import (assert_lse_close, assert_o_close, assert_pool_contents_
 pytestmark = pytest.mark.gpu
 
 
-def test_config1_pi05_frame_all_64_steps_two_layers():
+@pytest.mark.parametrize("fold", [False, True], ids=["separate_append", "folded_append"])
+def test_config1_pi05_frame_all_64_steps_two_layers(fold):
     w = synth.pi05_frame()
-    gw, g, ow, o = run_both(w, layers=[0, 17])
+    gw, g, ow, o = run_both(w, layers=[0, 17], fold_append=fold)
     gw.close()
     steps = [r for op, r in zip(w["trace"], g) if op["op"] == "step"]
     assert len(steps) == 64 and steps[0]["O"][17].shape == (51, 8, 256)
@@ -71,13 +72,15 @@ def gw_free(gw):
     return B.oxy_pool_stats(gw.pool)[0]
 
 
-def test_config4_stress_full_size_sampled_against_oracle():
-    """Full stress geometry in the launch configuration the benchmark times (default split):
-    64 streams, histories ~U{1..2048}, 8 shared 2048-token prefixes, fragmented pool.  The
-    oracle recomputes a sample of items one by one from its un-paged lists."""
+@pytest.mark.parametrize("fold", [True, False], ids=["folded_append", "separate_append"])
+def test_config4_stress_full_size_sampled_against_oracle(fold):
+    """Full stress geometry in the launch configuration the benchmark times (default split, the
+    new rows appended by the work items; and with the separate append): 64 streams, histories
+    ~U{1..2048}, 8 shared 2048-token prefixes, fragmented pool.  The oracle recomputes a sample
+    of items one by one from its un-paged lists."""
     w = synth.stress(n_layers=18, mixed_steps=2)
     layers = [0, 17]
-    gw, g, ow, o = run_both(w, layers=layers, oracle_steps=set(), want_lse=True)
+    gw, g, ow, o = run_both(w, layers=layers, oracle_steps=set(), want_lse=True, fold_append=fold)
     try:
         op = w["trace"][-1]
         res = g[-1]
