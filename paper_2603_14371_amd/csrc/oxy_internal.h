@@ -47,8 +47,7 @@ struct AttnArgs {
   const void* q;            // [n_q][8][256] bf16
   void* out;                // [n_q][8][256] bf16
   float* lse;               // [n_q][8] or null
-  const int32_t* work;      // [n_work][8]
-  const int32_t* tok_list;
+  const int32_t* work;      // [n_work][32]: one 128-byte record per work item
   const int32_t* tables;
   const int32_t* part_off;  // [n_q]
   const int32_t* n_parts;   // [n_q]

@@ -311,7 +311,7 @@ __device__ __forceinline__ u32x4 value_mask(const int left, const int g) {
 
 
 struct WorkItem {
-  int tok_off, n_tok, kv_begin, kv_end, q0, part_idx;
+  int n_tok, kv_begin, kv_end, q0, part_idx;
   const int32_t* tbl;
   int rec;   // this lane's word of the 32-word record (lanes 32..63 mirror 0..31)
 };
@@ -739,7 +739,6 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   // one 128-byte load brings the whole record; its fields are read out lane-wise
   WorkItem wi;
   wi.rec = a.work[(size_t)blockIdx.x * kWorkWords + (threadIdx.x & 31)];
-  wi.tok_off = __builtin_amdgcn_readlane(wi.rec, W_TOK_OFF);
   wi.n_tok = __builtin_amdgcn_readlane(wi.rec, W_N_TOK);
   wi.tbl = a.tables + __builtin_amdgcn_readlane(wi.rec, W_TBL_OFF);
   wi.kv_begin = __builtin_amdgcn_readlane(wi.rec, W_KV_BEGIN);

@@ -773,7 +773,6 @@ oxy::AttnArgs attn_args(const oxy_pool* p, const oxy_batch* b, int32_t layer, co
   a.out = out;
   a.lse = lse;
   a.work = d + b->off_work;
-  a.tok_list = d + b->off_toks;
   a.tables = d + b->off_tables;
   a.part_off = d + b->off_part_off;
   a.n_parts = d + b->off_n_parts;
