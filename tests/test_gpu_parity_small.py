@@ -67,3 +67,42 @@ def test_split_sizes_including_block_table_fallback(tile, stream):
     w = synth.tiny(prefix_len=1100, chunk=37, prior=700, n_layers=2)
     gw, g, ow, o = run_both(w, split_tokens=tile, stream_split_tokens=stream, max_partials=4096)
     _finish(gw, ow)
+
+
+@pytest.mark.parametrize("fold", [False, True], ids=["separate_append", "folded_append"])
+def test_histories_around_page_step_and_split_boundaries(fold):
+    """Decode streams whose own histories end just before, on and just after page (16), step
+    (32) and split (64) boundaries, then take one and two new tokens; with and without a
+    prefix whose last page is partial."""
+    from paper_2603_14371_amd.synth import _TraceBuilder, _workload, DECODE, ACTION
+    b = _TraceBuilder()
+    pid = b.prefix(70)
+    lens = [1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193]
+    sids = [b.stream(pid if i % 2 == 0 else -1, DECODE) for i in range(len(lens))]
+    b.step([(s, n) for s, n in zip(sids, lens)], attend=False)
+    b.step([(s, 1) for s in sids])
+    b.step([(s, 2) for s in sids])
+    b.step([(s, 1) for s in sids[::-1]])
+    w = _workload("boundaries", 515, 2, 512, b.trace)
+    gw, g, ow, o = run_both(w, split_tokens=64, stream_split_tokens=64, poison=True,
+                            fold_append=fold, max_partials=4096)
+    _finish(gw, ow)
+
+
+def test_a_query_that_sees_only_itself_returns_its_value_row():
+    """No prefix, empty history, one new token: the visible set is the token itself, so O is
+    its V row exactly (bf16 in, bf16 out) and LSE is its own logit."""
+    from paper_2603_14371_amd.synth import _TraceBuilder, _workload, DECODE, ACTION
+    b = _TraceBuilder()
+    d, a = b.stream(-1, DECODE), b.stream(-1, ACTION)
+    b.step([(d, 1), (a, 1)])
+    w = _workload("self_only", 808, 1, 64, b.trace)
+    gw, g, ow, o = run_both(w, fold_append=True)
+    try:
+        src = synth.DataSource(w["seed"], w["sigma"])
+        v = src(w["trace"][-1]["data"], 0, "v", 2)
+        for tok in range(2):
+            for h in range(8):
+                assert np.array_equal(g[-1]["O"][0][tok, h], v[tok])
+    finally:
+        gw.close()
