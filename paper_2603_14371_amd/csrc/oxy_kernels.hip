@@ -228,6 +228,7 @@ constexpr int kOffVA = 2 * kPageBytes + 256;
 constexpr int kOffVB = kOffVA + kPageBytes;
 constexpr int kStageBytes = kOffVB + kPageBytes;      // 33024
 constexpr int kMergeStride = kDim + 4;                // floats per row in the LDS merge buffer
+constexpr int kEpilogueStride = kDim * 2 + 16;        // bytes per fp16 row in the tile epilogue
 constexpr int kSmemBytes = 4 * 16 * kMergeStride * 4; // 66560 >= 2 * kStageBytes
 static_assert(2 * kStageBytes <= kSmemBytes, "two stages must fit");
 constexpr float kGrow = 8.f;  // the reference max only moves when a logit exceeds it by 2^8
@@ -338,6 +339,9 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   const bool wave_active = 2 * wv < wi.n_tok;
   const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
   const int qpos = wi.q0 + ts;
+  // first partial slot of this row's token: needed only at the end, loaded now so that the
+  // epilogue does not wait for it
+  const int part_base = a.part_off[tok];
   u32x4 qf[8];
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
@@ -364,7 +368,10 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       // thread tid holds chunks tid and tid+256 of each page: K chunk = 8 dims of one key (one
       // 16-byte load from the row), V chunk = one dim of 8 keys (eight 2-byte loads).  Positions
       // at or beyond the split's end re-read its last row; they are masked like stale slots.
-      const int pos0 = wi.kv_begin + (real ? 32 * s : 0), last = wi.kv_end - 1;
+      // A step past the end loads nothing here: these gathers are expensive, the rows sit in L2,
+      // and a fresh tile has few steps, so the wait that a conditional load costs is cheap.
+      if (!real) return;
+      const int pos0 = wi.kv_begin + 32 * s, last = wi.kv_end - 1;
       const uint16_t* kn = (const uint16_t*)a.k_new + (size_t)row0 * kDim;
       const uint16_t* vn = (const uint16_t*)a.v_new + (size_t)row0 * kDim;
       const int kkey = ((tid >> 5) & 1) * 8 + (tid & 7);
@@ -533,17 +540,29 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(acc[c][e]));
   amax = row_max4(amax);
   const float inv = amax > 0.f ? 1.f / amax : 0.f;
-  if (row_valid) {
-    const size_t slot = (size_t)a.part_off[tok] + wi.part_idx;
-    uint16_t* dst = a.part_acc + (slot * kHeads + h) * kDim;
-    typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+  // Each lane holds 4-dim pieces of its row; written as they are, a store would touch 16 rows
+  // with 32 bytes each.  The rows go through LDS instead (the stages are free after the loop's
+  // last barrier; every wavefront uses a region of its own, so no barrier is needed) and leave
+  // as whole rows: 32 lanes x 16 bytes per row.
+  typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+  char* ep = smem + wv * (16 * kEpilogueStride);
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      const u32x2 v = {pack_f16(acc[c][0] * inv, acc[c][1] * inv),
-                       pack_f16(acc[c][2] * inv, acc[c][3] * inv)};
-      *(u32x2*)(dst + 16 * c + 4 * g) = v;
-    }
-    if (g == 0) *(f32x4*)(a.part_ml + (slot * kHeads + h) * 4) = (f32x4){m, l, amax, 0.f};
+  for (int c = 0; c < 16; ++c) {
+    const u32x2 v = {pack_f16(acc[c][0] * inv, acc[c][1] * inv),
+                     pack_f16(acc[c][2] * inv, acc[c][3] * inv)};
+    *(u32x2*)(ep + n * kEpilogueStride + (16 * c + 4 * g) * 2) = v;
+  }
+  asm volatile("" ::: "memory");   // the reads below are of another type: keep them behind the writes
+  const int slot_lane = part_base + wi.part_idx;   // of this lane's row n
+  if (row_valid && g == 0)
+    *(f32x4*)(a.part_ml + ((size_t)slot_lane * kHeads + h) * 4) = (f32x4){m, l, amax, 0.f};
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int row = 2 * it + (lane >> 5);              // row of this wavefront's 16
+    const int slot_row = __shfl(slot_lane, row);       // lane `row` (g = 0) owns that row
+    const u32x4 v = *(const u32x4*)(ep + row * kEpilogueStride + (lane & 31) * 16);
+    if (2 * wv + (row >> 3) < wi.n_tok)
+      *(u32x4*)(a.part_acc + ((size_t)slot_row * kHeads + (row & 7)) * kDim + (lane & 31) * 8) = v;
   }
 }
 
@@ -559,6 +578,10 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const bool row_valid = ts < wi.n_tok;
   const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
   const int qpos = wi.q0 + ts;
+  // In the epilogue thread tid writes 16 dims of row tid / 16; the first partial slot of that
+  // row's token is loaded now so that the epilogue does not wait for it.
+  const int otok = __shfl(wi.rec, 8 + ((tid >> 7) < wi.n_tok ? (tid >> 7) : 0));
+  const int part_base = a.part_off[otok];
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
 #pragma unroll
@@ -688,8 +711,9 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     sml[wv][n][1] = l;
   }
   __syncthreads();
-  const int r = tid >> 4, seg = (tid & 15) * 16;
-  const int otok = __shfl(wi.rec, 8 + (r >> 3));
+  // thread tid: row tid / 16, dims [8t, 8t+8) and [128+8t, 128+8t+8) with t = tid % 16, so that
+  // the 16 threads of a row write 256 contiguous bytes per store
+  const int r = tid >> 4, seg = (tid & 15) * 8;
   if ((r >> 3) < wi.n_tok) {
     const float ninf = -__builtin_inff();
     float big = ninf;
@@ -701,16 +725,17 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       wgt[w] = (sml[w][r][0] == ninf) ? 0.f : fast_exp2(sml[w][r][0] - big);
       total = __builtin_fmaf(wgt[w], sml[w][r][1], total);
     }
-    const size_t slot = (size_t)a.part_off[otok] + wi.part_idx;
+    const size_t slot = (size_t)part_base + wi.part_idx;
     uint16_t* dst = a.part_acc + (slot * kHeads + (r & 7)) * kDim + seg;
     f32x4 o[4];
     float amax = 0.f;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+      const int d = seg + 4 * (q & 1) + 128 * (q >> 1);
       o[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const f32x4 x = *(const f32x4*)(sm + (w * 16 + r) * kMergeStride + seg + 4 * q);
+        const f32x4 x = *(const f32x4*)(sm + (w * 16 + r) * kMergeStride + d);
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[q][e] = __builtin_fmaf(wgt[w], x[e], o[q][e]);
       }
@@ -726,7 +751,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     const u32x4 hi = {pack_f16(o[2][0] * inv, o[2][1] * inv), pack_f16(o[2][2] * inv, o[2][3] * inv),
                       pack_f16(o[3][0] * inv, o[3][1] * inv), pack_f16(o[3][2] * inv, o[3][3] * inv)};
     *(u32x4*)(dst) = lo;
-    *(u32x4*)(dst + 8) = hi;
+    *(u32x4*)(dst + 128) = hi;
     if ((tid & 15) == 0)
       *(f32x4*)(a.part_ml + (slot * kHeads + (r & 7)) * 4) = (f32x4){big, total, amax, 0.f};
   }
