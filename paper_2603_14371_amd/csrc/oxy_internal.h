@@ -26,7 +26,9 @@ enum { PATH_STREAM = 0,  // <=2 query tokens (16 rows): 4 wavefronts split the k
 // The path sits in the low four bits of word W_PATH.  kPathFresh marks an own-phase tile of an
 // item whose own history was empty before this step: all of its keys are rows of this step's
 // k_new / v_new, row = (word >> kPathRowShift) + own position.
-constexpr int kPathMask = 15, kPathFresh = 16, kPathRowShift = 8;
+// kPathAppends marks a streaming work item on an item's own pages: its query tokens are the new
+// rows that a folded append has to write (a streaming item on prefix pages appends nothing).
+constexpr int kPathMask = 15, kPathFresh = 16, kPathAppends = 32, kPathRowShift = 8;
 
 struct InlineIds {
   int32_t v[kMaxInlineBlocks];

@@ -570,7 +570,7 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
 // four wavefronts take the 32-key steps of the split round-robin, stream their pages straight
 // into registers one step ahead, and combine their four results through LDS.
 __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& wi, char* smem,
-                                            float (*sml)[16][2], char* qs) {
+                                            float (*sml)[16][2], char* qs, const bool appends) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int n = lane & 15, g = lane >> 4;
@@ -628,7 +628,8 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   int32_t row_slot[2] = {0, 0};
   bool row_mine[2] = {false, false};
   bool early = false;
-  if (a.k_new) {
+  const bool fold = a.k_new && appends;
+  if (fold) {
     const int pos0 = (wi.q0 == kNoCausal ? 0 : wi.q0);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -663,7 +664,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       *(u32x4*)(qs + j * 1024 + lane * 16) = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
     }
   }
-  if (a.k_new && !early) {
+  if (fold && !early) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
       if (row_mine[t]) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
@@ -780,7 +781,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
     else
       tile_path<false>(a, wi, smem, 0);
   } else if (path == PATH_STREAM) {
-    stream_path(a, wi, smem, sml, qs);
+    stream_path(a, wi, smem, sml, qs, (path_word & kPathAppends) != 0);
   } else {
     return;   // padding record
   }

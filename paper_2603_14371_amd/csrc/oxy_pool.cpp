@@ -478,10 +478,16 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     //   own phase    -> items with <= 2 new tokens (decode) stream their own pages;
     //                   larger items (action chunks, multi-token decode) use tiles of 8.
     const int32_t tile_tok = 8;
+    // A decode item (<= 2 new tokens) on a short prefix streams the prefix pages on its own,
+    // like its own pages: four steps in flight at once instead of a tile's two, and with few
+    // queries per prefix there is little to share.  On a long prefix it joins the tiles, which
+    // fetch the prefix once for all queries attached to it.
+    constexpr int32_t kStreamPrefixMax = 1024;
     struct Group {
       int32_t pid;
       const Prefix* px;
       std::vector<int32_t> toks;
+      std::vector<std::pair<int32_t, int32_t>> solo;   // (first token, count) of streaming items
     };
     std::vector<Group> groups;   // in order of first appearance; a batch touches few prefixes
     groups.reserve(16);
@@ -497,10 +503,14 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       if (!g) {
         const Prefix& px = p->prefixes.at(pid);
         if (px.len == 0) continue;
-        groups.push_back({pid, &px, {}});
+        groups.push_back({pid, &px, {}, {}});
         g = &groups.back();
       }
-      for (int32_t t = 0; t < pl.new_len - pl.old_len; ++t) g->toks.push_back(pl.tok0 + t);
+      const int32_t n_new = pl.new_len - pl.old_len;
+      if (n_new <= 2 && g->px->len <= kStreamPrefixMax)
+        g->solo.push_back({pl.tok0, n_new});
+      else
+        for (int32_t t = 0; t < n_new; ++t) g->toks.push_back(pl.tok0 + t);
     }
     for (const Group& g : groups) {
       const Prefix& px = *g.px;
@@ -518,6 +528,14 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
                    oxy::kNoCausal, s, oxy::PATH_TILE);
       }
       for (int32_t t : g.toks) n_parts[t] = nsplit;
+      for (const auto& so : g.solo) {
+        const int32_t tok_off = (int32_t)toks.size();
+        for (int32_t t = 0; t < so.second; ++t) toks.push_back(so.first + t);
+        for (int32_t s = 0; s < nsplit; ++s)
+          add_work(tok_off, so.second, tbl_off, s * split, std::min(px.len, (s + 1) * split),
+                   oxy::kNoCausal, s, oxy::PATH_STREAM);
+        for (int32_t t = 0; t < so.second; ++t) n_parts[so.first + t] = nsplit;
+      }
     }
     for (const Plan& pl : plan) {
       const int32_t tbl_off = tbl_words;
@@ -525,8 +543,8 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       tbl_words += blocks_for(pl.new_len);
       const int32_t n_new = pl.new_len - pl.old_len;
       const bool causal = pl.s->kind == OXY_KIND_DECODE;
-      int32_t path = n_new <= 2 ? oxy::PATH_STREAM : oxy::PATH_TILE;
-      if (path == oxy::PATH_TILE) {
+      int32_t path = n_new <= 2 ? (oxy::PATH_STREAM | oxy::kPathAppends) : oxy::PATH_TILE;
+      if ((path & oxy::kPathMask) == oxy::PATH_TILE) {
         if (pl.old_len == 0)
           path |= oxy::kPathFresh | (pl.tok0 << oxy::kPathRowShift);
         else
