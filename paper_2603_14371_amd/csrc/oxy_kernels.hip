@@ -502,9 +502,8 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       }
     }
   }
-  fetch(0, st0);
-  fetch(1, st1);
-  {  // the query rows come after the first pages are on their way (they are needed later)
+  {  // the query rows are requested first: loads complete in order per wavefront, and the
+     // first product should wait for step 0 only, not for step 1 as well
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -512,6 +511,9 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       qf[j] = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
+  fetch(0, st0);
+  fetch(1, st1);
   __builtin_amdgcn_sched_barrier(0);
   sanitize(0, st0);
   commit(0, st0);
@@ -595,27 +597,26 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const int ids = split_block_ids(wi, lane, npg);
   const int lane_k = (g * 8 + (n & 7)) * 16;
   const int lane_v = kPageBytes + ((g & 1) * 16 + n) * 16;
-  // Always sixteen loads per call and no conditional call (see tile_path): a step past the end
-  // re-reads the same 16 B sixteen times, a missing page B re-reads page A; neither is used.
+  // A wavefront has at most one step in flight beyond the one it computes, and it waits for all
+  // of it before the next product, so (unlike the tile path) nothing is lost when the load of
+  // a step past the end is simply skipped; a missing page B re-reads page A and is masked.
   auto load_k = [&](const int s) {
-    const bool real = s < nsteps;
-    const int pi = real ? 2 * s : 0;
-    const int o = real ? 512 : 0;
+    if (s >= nsteps) return;
+    const int pi = 2 * s;
     const int blk_a = __builtin_amdgcn_readlane(ids, pi);
-    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((n >> 3) ? blk_b : blk_a) * kBlockBytes + lane_k;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) kr[i] = *(const u32x4*)(p + i * o);
+    for (int i = 0; i < 16; ++i) kr[i] = *(const u32x4*)(p + i * 512);
   };
   auto load_v = [&](const int s) {
-    const bool real = s < nsteps;
-    const int pi = real ? 2 * s : 0;
-    const int o = real ? 512 : 0;
+    if (s >= nsteps) return;
+    const int pi = 2 * s;
     const int blk_a = __builtin_amdgcn_readlane(ids, pi);
-    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((g >> 1) ? blk_b : blk_a) * kBlockBytes + lane_v;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * o);
+    for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * 512);
   };
   DBG_MARK(1);
   // Folded append: the query tokens of a streaming item are its new rows.  Those inside this
@@ -649,21 +650,24 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       __syncthreads();
     }
   }
-  int s = wv;
-  load_k(s);
-  load_v(s);
   // The 16 query rows are the same for all four wavefronts: their MFMA fragments live in LDS
-  // (registers are needed for the pages in flight).  Staged after the first pages are on
-  // their way, so the barrier costs no memory latency of its own.
+  // (registers are needed for the pages in flight).  The query loads are issued BEFORE the first
+  // pages: loads complete in order per wavefront, so the barrier below then waits for the
+  // queries only, not for the slowest wavefront's first 32 KiB.
+  u32x4 qtmp[2];
   {
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const int j = 2 * wv + jj;
-      *(u32x4*)(qs + j * 1024 + lane * 16) = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
-    }
+    for (int jj = 0; jj < 2; ++jj)
+      qtmp[jj] = row_valid ? *(const u32x4*)(qrow + (2 * wv + jj) * 64 + g * 16) : z;
   }
+  int s = wv;
+  load_k(s);
+  load_v(s);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) *(u32x4*)(qs + (2 * wv + jj) * 1024 + lane * 16) = qtmp[jj];
   if (fold && !early) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -684,6 +688,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     u32x4 pf, pl;
     softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
                  pf, pl);
+    if (s == wv) DBG_MARK(8);
     __builtin_amdgcn_sched_barrier(0);  // the next K pages reuse kr[]: issue only after S
     load_k(s + 4);
     __builtin_amdgcn_sched_barrier(0);
@@ -695,6 +700,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     }
 #pragma unroll
     for (int c = 0; c < 16; ++c) acc[c] = mfma16(vr[c], pl, mfma16(vr[c], pf, acc[c]));
+    if (s == wv) DBG_MARK(9);
     __builtin_amdgcn_sched_barrier(0);  // likewise vr[]
     load_v(s + 4);
     __builtin_amdgcn_sched_barrier(0);
