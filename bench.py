@@ -397,6 +397,43 @@ def bench_arrivals(device, split_tokens, frames=24, warm=12, k=10, s_act=10, chu
                 "actions_per_s": round(n_obs * chunk / sum(t_frames), 1),
                 "decode_tokens_per_s": round(n_dec_items / sum(t_frames), 1),
             }
+        # the paper's reference baseline: isolated sequential execution, no sharing, no batching
+        # (one prefill copy per task, action steps alone, then the request alone to completion)
+        t_frames, n_obs, n_dec = [], 0, 0
+        for t, targets in enumerate(arrivals):
+            if t < warm - 2:          # nothing carries over between frames here
+                continue
+            torch.cuda.synchronize(device)
+            t0 = time.perf_counter()
+            for n in targets:
+                pids = []
+                for _ in range(2):
+                    pid = B.oxy_prefix_create(gw.pool)
+                    for layer in range(L):
+                        B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(),
+                                            pk[layer, 1].data_ptr(), prefix_len, 0, stream)
+                    pids.append(pid)
+                act = B.oxy_stream_create(gw.pool, pids[0], B.KIND_ACTION)
+                dec = B.oxy_stream_create(gw.pool, pids[1], B.KIND_DECODE)
+                for _ in range(s_act):
+                    runner.step([(act, chunk)])
+                    torch.cuda.synchronize(device)
+                for _ in range(n):
+                    runner.step([(dec, 1)])
+                    torch.cuda.synchronize(device)
+                B.oxy_stream_release(gw.pool, act)
+                B.oxy_stream_release(gw.pool, dec)
+                for pid in pids:
+                    B.oxy_prefix_release(gw.pool, pid)
+            if t >= warm:
+                t_frames.append(time.perf_counter() - t0)
+                n_obs += len(targets)
+                n_dec += sum(targets)
+        T = float(np.mean(t_frames))
+        res["isolated_baseline"] = {
+            "frame_ms": round(T * 1e3, 3), "action_hz_per_request": round(1.0 / T, 1),
+            "avg_decode_batch": 1.0, "actions_per_s": round(n_obs * chunk / sum(t_frames), 1),
+            "decode_tokens_per_s": round(n_dec / sum(t_frames), 1)}
         out[pname] = res
     gw.close()
     return out
