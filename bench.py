@@ -639,8 +639,8 @@ def main():
                     help="also launch plain 256 MiB copies (calibration of traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (sharding by prefix group is described in "
-              "DESIGN.md); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard by prefix group: a "
+              "prefix and the streams attached to it per GPU); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
