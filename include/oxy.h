@@ -106,7 +106,7 @@ typedef struct {
   size_t workspace_bytes;
   const int32_t *free_order;/* HOST, optional permutation of [0,num_blocks); copied          */
   int32_t max_live_batches; /* descriptors that may exist at once (0 -> 2)                   */
-  int32_t max_q_tokens;     /* query tokens per attended batch (0 -> 1024)                   */
+  int32_t max_q_tokens;     /* query tokens per attended batch (0 -> 1024; at most 2^20)     */
   int32_t max_append_tokens;/* new tokens per batch, append-only ones included (0 -> 16*num_blocks) */
   int32_t max_work_items;   /* attention work items per batch (0 -> 16384)                   */
   int32_t max_partials;     /* per-token split results per batch (0 -> 32*max_q_tokens)      */

@@ -111,6 +111,8 @@ bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
   // split_tokens == 0 stays 0: the tile path then sizes its splits from the length of the KV
   // source alone (see tile_split_for), which keeps an item's arithmetic independent of its batch
   if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens ? c->split_tokens : 256;
+  // query token ids travel in 23 bits of a work-record word (kPathRowShift)
+  if (c->max_q_tokens > (1 << 20) || c->max_append_tokens > (1 << 26)) return false;
   if (c->max_live_batches < 1 || c->max_live_batches > 64 || c->max_q_tokens < 1 ||
       c->max_append_tokens < 1 || c->max_work_items < 1 || c->max_partials < 1 ||
       (c->split_tokens != 0 && (c->split_tokens < 32 || c->split_tokens % 32 != 0)) ||
