@@ -246,9 +246,9 @@ def bench_frame(device, split_tokens, frames=3):
         for op in ops:
             t0 = time.perf_counter()
             if op["op"] == "prefix_append":
-                for layer in range(L):
-                    B.oxy_prefix_append(gw.pool, op["pid"], layer, pk[layer, 0].data_ptr(),
-                                        pk[layer, 1].data_ptr(), 832, 0, stream)
+                B.oxy_prefix_append_layers(gw.pool, op["pid"], 0, L, pk[0, 0].data_ptr(),
+                                           pk[0, 1].data_ptr(), pk.stride(0) * 2, 832,
+                                           0, stream)
                 torch.cuda.synchronize(device)
                 marks["prefix"] += time.perf_counter() - t0
             elif op["op"] == "step":
@@ -304,9 +304,9 @@ def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
             t0 = time.perf_counter()
             for op in w["trace"]:
                 if op["op"] == "prefix_append":
-                    for layer in range(L):
-                        B.oxy_prefix_append(gw.pool, op["pid"], layer, pk[layer, 0].data_ptr(),
-                                            pk[layer, 1].data_ptr(), op["n"], op["pos0"], stream)
+                    B.oxy_prefix_append_layers(gw.pool, op["pid"], 0, L, pk[0, 0].data_ptr(),
+                                               pk[0, 1].data_ptr(), pk.stride(0) * 2, op["n"],
+                                               op["pos0"], stream)
                 elif op["op"] == "step":
                     runner.step(op["items"])
                 elif "release" in op["op"]:
@@ -371,9 +371,9 @@ def bench_arrivals(device, split_tokens, frames=24, warm=12, k=10, s_act=10, chu
                 t0 = time.perf_counter()
                 for n in targets:
                     pid = B.oxy_prefix_create(gw.pool)
-                    for layer in range(L):
-                        B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(),
-                                            pk[layer, 1].data_ptr(), prefix_len, 0, stream)
+                    B.oxy_prefix_append_layers(gw.pool, pid, 0, L, pk[0, 0].data_ptr(),
+                                               pk[0, 1].data_ptr(), pk.stride(0) * 2, prefix_len,
+                                               0, stream)
                     B.oxy_sched_admit(sched, pid, n)
                 while True:
                     items, n_action = B.oxy_sched_next_step(sched)
@@ -409,9 +409,9 @@ def bench_arrivals(device, split_tokens, frames=24, warm=12, k=10, s_act=10, chu
                 pids = []
                 for _ in range(2):
                     pid = B.oxy_prefix_create(gw.pool)
-                    for layer in range(L):
-                        B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(),
-                                            pk[layer, 1].data_ptr(), prefix_len, 0, stream)
+                    B.oxy_prefix_append_layers(gw.pool, pid, 0, L, pk[0, 0].data_ptr(),
+                                               pk[0, 1].data_ptr(), pk.stride(0) * 2, prefix_len,
+                                               0, stream)
                     pids.append(pid)
                 act = B.oxy_stream_create(gw.pool, pids[0], B.KIND_ACTION)
                 dec = B.oxy_stream_create(gw.pool, pids[1], B.KIND_DECODE)
@@ -461,9 +461,8 @@ def bench_calibration(device, split_tokens, targets_hz=(350.0, 300.0, 250.0), n_
 
     def new_prefix():
         pid = B.oxy_prefix_create(gw.pool)
-        for layer in range(L):
-            B.oxy_prefix_append(gw.pool, pid, layer, pk[layer, 0].data_ptr(), pk[layer, 1].data_ptr(),
-                                prefix_len, 0, stream)
+        B.oxy_prefix_append_layers(gw.pool, pid, 0, L, pk[0, 0].data_ptr(), pk[0, 1].data_ptr(),
+                                   pk.stride(0) * 2, prefix_len, 0, stream)
         return pid
 
     def timed(items):

@@ -142,6 +142,12 @@ int32_t oxy_prefix_create(oxy_pool *pool, int32_t *prefix_id); /* holds the crea
  * reached (by whichever layer comes first).  SEALED once a stream is attached. */
 int32_t oxy_prefix_append(oxy_pool *pool, int32_t prefix_id, int32_t layer, const void *k,
                           const void *v, int32_t n_tokens, int32_t pos0, void *hip_stream);
+/* The same for layers [layer_begin, layer_end) in one call and one launch (the KV of a whole
+ * prefill, Eq. 1): layer l reads k + (l - layer_begin) * layer_stride and v likewise (bytes). */
+int32_t oxy_prefix_append_layers(oxy_pool *pool, int32_t prefix_id, int32_t layer_begin,
+                                 int32_t layer_end, const void *k, const void *v,
+                                 size_t layer_stride, int32_t n_tokens, int32_t pos0,
+                                 void *hip_stream);
 /* Fork (an extension for observations of consecutive frames that begin with the same history
  * segment): *prefix_id is a new prefix whose tokens 0..n_tokens-1 ARE the parent's — it lists the
  * parent's first n_tokens/16 blocks (refcount + 1 each, no copy).  n_tokens must be a multiple of

@@ -24,7 +24,8 @@ SCHED_BATCHED, SCHED_UNBATCHED, SCHED_UPPER_BOUND = 0, 1, 2
 
 EXPORTS = [
     "oxy_version", "oxy_last_error", "oxy_kv_bytes", "oxy_workspace_bytes", "oxy_pool_create",
-    "oxy_pool_destroy", "oxy_prefix_create", "oxy_prefix_append", "oxy_prefix_fork",
+    "oxy_pool_destroy", "oxy_prefix_create", "oxy_prefix_append", "oxy_prefix_append_layers",
+    "oxy_prefix_fork",
     "oxy_prefix_release",
     "oxy_stream_create", "oxy_stream_release", "oxy_stream_rewind", "oxy_batch_build",
     "oxy_stream_append", "oxy_mixed_attention", "oxy_step_layers", "oxy_append_attention",
@@ -91,6 +92,7 @@ def lib():
             "oxy_pool_destroy": [vp],
             "oxy_prefix_create": [vp, pi32],
             "oxy_prefix_append": [vp, i32, i32, vp, vp, i32, i32, vp],
+            "oxy_prefix_append_layers": [vp, i32, i32, i32, vp, vp, ctypes.c_size_t, i32, i32, vp],
             "oxy_prefix_fork": [vp, i32, i32, pi32],
             "oxy_prefix_release": [vp, i32],
             "oxy_stream_create": [vp, i32, i32, pi32],
@@ -194,6 +196,13 @@ def oxy_prefix_create(pool):
 def oxy_prefix_append(pool, prefix_id, layer, k_ptr, v_ptr, n_tokens, pos0, stream):
     _check(lib().oxy_prefix_append(pool, prefix_id, layer, k_ptr or None, v_ptr or None, n_tokens,
                                    pos0, stream or None))
+
+
+def oxy_prefix_append_layers(pool, prefix_id, layer_begin, layer_end, k_ptr, v_ptr, layer_stride,
+                             n_tokens, pos0, stream):
+    _check(lib().oxy_prefix_append_layers(pool, prefix_id, layer_begin, layer_end, k_ptr or None,
+                                          v_ptr or None, layer_stride, n_tokens, pos0,
+                                          stream or None))
 
 
 def oxy_prefix_fork(pool, parent_prefix_id, n_tokens):

@@ -38,8 +38,11 @@ struct InlineIds {
 hipError_t launch_append(const void* k_new, const void* v_new, const int32_t* d_slots,
                          int32_t n_tokens, void* layer_base, hipStream_t s);
 // Same, slots = blocks.v[(pos0+t)/16]*16 + (pos0+t)%16 with the block ids passed by value.
+// n_layers consecutive layers in one launch: layer i reads k_new/v_new + i*src_layer_stride and
+// writes layer_base + i*pool_layer_stride (bytes).
 hipError_t launch_append_inline(const void* k_new, const void* v_new, const InlineIds& blocks,
-                                int32_t pos0, int32_t n_tokens, void* layer_base, hipStream_t s);
+                                int32_t pos0, int32_t n_tokens, void* layer_base, int32_t n_layers,
+                                size_t src_layer_stride, size_t pool_layer_stride, hipStream_t s);
 // Gather rows back to natural order; slot ids passed by value (<= kMaxInlineBlocks per call).
 hipError_t launch_gather_inline(const void* layer_base, const InlineIds& slots, int32_t n,
                                 void* k_out, void* v_out, hipStream_t s);

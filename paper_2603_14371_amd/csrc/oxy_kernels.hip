@@ -132,13 +132,20 @@ __global__ __launch_bounds__(256) void append_kernel(const uint16_t* __restrict_
 // A block that is covered completely is written as whole 16-byte chunks (V transposed through
 // LDS); a partly covered block falls back to the per-row scatter so that nothing else in the
 // page is touched.
+// blockIdx.y = layer relative to the first one: sources advance by src_layer_stride bytes, the
+// pool by pool_layer_stride bytes per layer.
 __global__ __launch_bounds__(256) void append_blocks_kernel(const uint16_t* __restrict__ k_new,
                                                             const uint16_t* __restrict__ v_new,
                                                             const InlineIds blocks, int32_t pos0,
                                                             int32_t n_tokens,
-                                                            char* __restrict__ layer_base) {
+                                                            char* __restrict__ layer_base,
+                                                            size_t src_layer_stride,
+                                                            size_t pool_layer_stride) {
   __shared__ __align__(16) uint16_t v_s[kPage][kDim + 8];   // +8: rows land in different banks
   const int t = threadIdx.x;
+  k_new = (const uint16_t*)((const char*)k_new + blockIdx.y * src_layer_stride);
+  v_new = (const uint16_t*)((const char*)v_new + blockIdx.y * src_layer_stride);
+  layer_base += blockIdx.y * pool_layer_stride;
   const int first_page = pos0 >> 4;
   const int page = first_page + blockIdx.x;
   const int lo = max(pos0, page * kPage), hi = min(pos0 + n_tokens, (page + 1) * kPage);
@@ -199,12 +206,14 @@ hipError_t launch_append(const void* k_new, const void* v_new, const int32_t* d_
 }
 
 hipError_t launch_append_inline(const void* k_new, const void* v_new, const InlineIds& blocks,
-                                int32_t pos0, int32_t n_tokens, void* layer_base, hipStream_t s) {
-  if (n_tokens <= 0) return hipSuccess;
+                                int32_t pos0, int32_t n_tokens, void* layer_base, int32_t n_layers,
+                                size_t src_layer_stride, size_t pool_layer_stride, hipStream_t s) {
+  if (n_tokens <= 0 || n_layers <= 0) return hipSuccess;
   // blocks.v[i] is the block of page (pos0 / 16 + i)
   const int32_t n_pages = ((pos0 + n_tokens + kPage - 1) >> 4) - (pos0 >> 4);
-  append_blocks_kernel<<<n_pages, 256, 0, s>>>((const uint16_t*)k_new, (const uint16_t*)v_new,
-                                               blocks, pos0, n_tokens, (char*)layer_base);
+  append_blocks_kernel<<<dim3(n_pages, n_layers), 256, 0, s>>>(
+      (const uint16_t*)k_new, (const uint16_t*)v_new, blocks, pos0, n_tokens, (char*)layer_base,
+      src_layer_stride, pool_layer_stride);
   return hipGetLastError();
 }
 

@@ -277,26 +277,29 @@ int32_t oxy_prefix_create(oxy_pool* p, int32_t* prefix_id) {
   return OXY_OK;
 }
 
-int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k, const void* v,
-                          int32_t n_tokens, int32_t pos0, void* hip_stream) {
-  if (!p) return fail(OXY_ERR_INVALID_ARG, "prefix_append: null pool");
+namespace {
+// Appends tokens [pos0, pos0+n) of layers [layer_begin, layer_end): blocks are allocated on first
+// touch, then one launch per 512 blocks covers all the layers.
+int32_t prefix_append_impl(oxy_pool* p, int32_t pid, int32_t layer_begin, int32_t layer_end,
+                           const void* k, const void* v, size_t src_layer_stride, int32_t n_tokens,
+                           int32_t pos0, void* hip_stream, const char* who) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "%s: null pool", who);
   auto it = p->prefixes.find(pid);
   if (it == p->prefixes.end() || !it->second.handle)
-    return fail(OXY_ERR_BAD_ID, "prefix_append: no prefix %d", pid);
+    return fail(OXY_ERR_BAD_ID, "%s: no prefix %d", who, pid);
   Prefix& px = it->second;
-  if (layer < 0 || layer >= p->cfg.n_layers || n_tokens < 1 || pos0 < 0 || pos0 > px.len ||
-      (int64_t)pos0 + n_tokens > (int64_t)kPage * p->cfg.num_blocks)
-    return fail(OXY_ERR_INVALID_ARG, "prefix_append: layer %d, n %d, pos0 %d (len %d)", layer,
-                n_tokens, pos0, px.len);
-  if (!p->host_only && (!k || !v)) return fail(OXY_ERR_INVALID_ARG, "prefix_append: null k/v");
-  if (px.sealed) return fail(OXY_ERR_SEALED, "prefix_append: prefix %d has streams attached", pid);
+  if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end || n_tokens < 1 ||
+      pos0 < 0 || pos0 > px.len || (int64_t)pos0 + n_tokens > (int64_t)kPage * p->cfg.num_blocks)
+    return fail(OXY_ERR_INVALID_ARG, "%s: layers [%d, %d), n %d, pos0 %d (len %d)", who, layer_begin,
+                layer_end, n_tokens, pos0, px.len);
+  if (!p->host_only && (!k || !v)) return fail(OXY_ERR_INVALID_ARG, "%s: null k/v", who);
+  if (px.sealed) return fail(OXY_ERR_SEALED, "%s: prefix %d has streams attached", who, pid);
   if (pos0 < px.frozen)
-    return fail(OXY_ERR_SEALED, "prefix_append: tokens below %d of prefix %d are shared with a fork",
+    return fail(OXY_ERR_SEALED, "%s: tokens below %d of prefix %d are shared with a fork", who,
                 px.frozen, pid);
   int32_t need = blocks_for(pos0 + n_tokens) - (int32_t)px.blocks.size();
   if (need > (int32_t)p->free_stack.size())
-    return fail(OXY_ERR_NO_BLOCKS, "prefix_append: need %d blocks, %zu free", need,
-                p->free_stack.size());
+    return fail(OXY_ERR_NO_BLOCKS, "%s: need %d blocks, %zu free", who, need, p->free_stack.size());
   for (int32_t i = 0; i < need; ++i) {
     int32_t b = p->free_stack.back();
     p->free_stack.pop_back();
@@ -308,6 +311,7 @@ int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k
   // device copy, at most kMaxInlineBlocks blocks per launch (block ids travel by value)
   const char* kp = (const char*)k;
   const char* vp = (const char*)v;
+  const size_t pool_layer_stride = (size_t)p->cfg.num_blocks * oxy::kBlockBytes;
   int32_t done = 0;
   while (done < n_tokens) {
     int32_t pos = pos0 + done;
@@ -317,14 +321,28 @@ int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k
     oxy::InlineIds ids;
     int32_t nb = blocks_for(pos + n) - first_block;
     for (int32_t i = 0; i < nb; ++i) ids.v[i] = px.blocks[first_block + i];
-    hipError_t e = oxy::launch_append_inline(kp + (size_t)done * oxy::kDim * 2,
-                                             vp + (size_t)done * oxy::kDim * 2, ids,
-                                             pos - first_block * kPage, n, layer_base(p, layer),
-                                             (hipStream_t)hip_stream);
+    hipError_t e = oxy::launch_append_inline(
+        kp + (size_t)done * oxy::kDim * 2, vp + (size_t)done * oxy::kDim * 2, ids,
+        pos - first_block * kPage, n, layer_base(p, layer_begin), layer_end - layer_begin,
+        src_layer_stride, pool_layer_stride, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "prefix_append: launch");
     done += n;
   }
   return OXY_OK;
+}
+}  // namespace
+
+int32_t oxy_prefix_append(oxy_pool* p, int32_t pid, int32_t layer, const void* k, const void* v,
+                          int32_t n_tokens, int32_t pos0, void* hip_stream) {
+  return prefix_append_impl(p, pid, layer, layer + 1, k, v, 0, n_tokens, pos0, hip_stream,
+                            "prefix_append");
+}
+
+int32_t oxy_prefix_append_layers(oxy_pool* p, int32_t pid, int32_t layer_begin, int32_t layer_end,
+                                 const void* k, const void* v, size_t layer_stride, int32_t n_tokens,
+                                 int32_t pos0, void* hip_stream) {
+  return prefix_append_impl(p, pid, layer_begin, layer_end, k, v, layer_stride, n_tokens, pos0,
+                            hip_stream, "prefix_append_layers");
 }
 
 int32_t oxy_prefix_fork(oxy_pool* p, int32_t parent_id, int32_t n_tokens, int32_t* prefix_id) {

@@ -106,3 +106,40 @@ def test_a_query_that_sees_only_itself_returns_its_value_row():
                 assert np.array_equal(g[-1]["O"][0][tok, h], v[tok])
     finally:
         gw.close()
+
+
+def test_prefix_append_of_all_layers_in_one_call_equals_per_layer_calls():
+    """oxy_prefix_append_layers (one launch for all layers, in two pieces with a ragged seam)
+    leaves the pool exactly as the per-layer calls do."""
+    import torch
+    from paper_2603_14371_amd import binding as B
+    from paper_2603_14371_amd.harness import GpuWorld, to_device_bf16
+    w = synth._workload("prefix_layers", 909, 3, 128, [], free_order=synth._perm(910, 128))
+    data = synth.DataSource(w["seed"])
+    rec = {"tag": 1, "tok0": 0, "n_total": 333}
+    pools = []
+    for all_layers in (False, True):
+        gw = GpuWorld(w, data, poison=True)
+        L = gw.n_layers
+        k = torch.stack([to_device_bf16(data(rec, l, "k", 333), gw.device) for l in range(L)])
+        v = torch.stack([to_device_bf16(data(rec, l, "v", 333), gw.device) for l in range(L)])
+        pid = B.oxy_prefix_create(gw.pool)
+        stream = torch.cuda.current_stream(gw.device).cuda_stream
+        for pos0, n in ((0, 200), (200, 133)):          # 200 = 12.5 pages: a ragged seam
+            if all_layers:
+                B.oxy_prefix_append_layers(gw.pool, pid, 0, L, k[0, pos0].data_ptr(),
+                                           v[0, pos0].data_ptr(), k.stride(0) * 2, n, pos0, stream)
+            else:
+                for l in range(L):
+                    B.oxy_prefix_append(gw.pool, pid, l, k[l, pos0].data_ptr(),
+                                        v[l, pos0].data_ptr(), n, pos0, stream)
+        torch.cuda.synchronize()
+        slots = gw.prefix_slots(pid)
+        assert len(slots) == 333
+        pools.append([gw.gather(l, slots) for l in range(L)])
+        for l in range(L):
+            assert np.array_equal(pools[-1][l][0], data(rec, l, "k", 333))
+            assert np.array_equal(pools[-1][l][1], data(rec, l, "v", 333))
+        gw.close()
+    for (ka, va), (kb, vb) in zip(*pools):
+        assert np.array_equal(ka, kb) and np.array_equal(va, vb)

@@ -239,3 +239,22 @@ def test_workspace_limits_are_reported_not_overrun():
     B.oxy_batch_destroy(b1)
     B.oxy_batch_destroy(b2)
     B.oxy_pool_destroy(pool)
+
+
+def test_prefix_append_layers_indexes_like_per_layer_appends():
+    pool = _host_pool(64, n_layers=3)
+    model = PoolModel(64, 16, 3)
+    pid = B.oxy_prefix_create(pool)
+    assert pid == model.prefix_create()
+    B.oxy_prefix_append_layers(pool, pid, 0, 3, 0, 0, 0, 70, 0, 0)
+    for layer in range(3):
+        model.prefix_append(pid, layer, 70, 0)
+    B.oxy_prefix_append_layers(pool, pid, 1, 3, 0, 0, 0, 30, 70, 0)
+    for layer in (1, 2):
+        model.prefix_append(pid, layer, 30, 70)
+    _same_state(pool, model)
+    for bad in ((2, 2), (-1, 2), (0, 4)):
+        with pytest.raises(B.OxyError) as e:
+            B.oxy_prefix_append_layers(pool, pid, bad[0], bad[1], 0, 0, 0, 5, 100, 0)
+        assert e.value.code == B.ERR_INVALID_ARG
+    B.oxy_pool_destroy(pool)
