@@ -497,7 +497,11 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     //   prefix phase -> tiles of up to 8 tokens sharing the prefix pages through LDS;
     //   own phase    -> items with <= 2 new tokens (decode) stream their own pages;
     //                   larger items (action chunks, multi-token decode) use tiles of 8.
-    const int32_t tile_tok = 8;
+    // Tokens per tile: 8 (64 MFMA rows, all four wavefronts) on long KV sources, where what
+    // counts is reading the pages once for as many queries as possible; 4 (two wavefronts
+    // compute, all four move pages) on short ones, where few workgroups exist anyway and a
+    // step is bound by the tile's own LDS reads and arithmetic.
+    auto tile_tok_for = [](int32_t source_len) { return source_len <= 1024 ? 4 : 8; };
     // A decode item (<= 2 new tokens) on a short prefix streams the prefix pages on its own,
     // like its own pages: four steps in flight at once instead of a tile's two, and with few
     // queries per prefix there is little to share.  On a long prefix it joins the tiles, which
@@ -539,6 +543,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       tbl_words += blocks_for(px.len);
       const int32_t split = tile_split_for(c, px.len);
       const int32_t nsplit = (px.len + split - 1) / split;
+      const int32_t tile_tok = tile_tok_for(px.len);
       for (size_t t0 = 0; t0 < g.toks.size(); t0 += tile_tok) {
         const int32_t n = (int32_t)std::min<size_t>(tile_tok, g.toks.size() - t0);
         const int32_t tok_off = (int32_t)toks.size();
@@ -570,7 +575,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         else
           foldable = false;   // old and new keys in one tile: only the separate append covers it
       }
-      const int32_t step_tok = n_new <= 2 ? 2 : tile_tok;
+      const int32_t step_tok = n_new <= 2 ? 2 : tile_tok_for(pl.new_len);
       const int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
         const int32_t n = std::min(step_tok, n_new - t0);

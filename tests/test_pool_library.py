@@ -181,18 +181,20 @@ def test_work_list_of_tiny_config():
         if op.get("attend", True):
             seen.append(_check_work_list(pool, model, op, batch))
             work = B.oxy_batch_work(batch)
-            # 10 chunk tokens on a 64-token prefix: tiles of up to 8 tokens x 1 split, shared
-            # pages (path 1), no causal base; the decode token streams the short prefix on its own
+            # 10 chunk tokens on a 64-token prefix: tiles of up to 4 tokens (short source) x 1
+            # split, shared pages (path 1), no causal base; the decode token streams the short
+            # prefix on its own
             work = work[work[:, 7] != 2]
             prefix_items = [r for r in work if r[5] == 0x3fffffff and r[4] == 64]
-            assert sorted((int(r[1]), int(r[7])) for r in prefix_items) == [(1, 0), (2, 1), (8, 1)]
+            assert sorted((int(r[1]), int(r[7])) for r in prefix_items) == [(1, 0), (2, 1), (4, 1),
+                                                                             (4, 1)]
             # the decode query sits at own position 4, sees own keys 0..4, streams its pages
             dec = [r for r in work if r[5] != 0x3fffffff]
             assert len(dec) == 1 and dec[0][5] == 4 and (dec[0][3], dec[0][4]) == (0, 5)
             assert dec[0][7] == 0
-            # action chunk: tiles of 8 + 2 tokens over its 10 own keys
+            # action chunk: tiles of 4 + 4 + 2 tokens over its 10 own keys
             act = [r for r in work if r[5] == 0x3fffffff and r[4] == 10]
-            assert sorted(int(r[1]) for r in act) == [2, 8] and all(r[7] == 1 for r in act)
+            assert sorted(int(r[1]) for r in act) == [2, 4, 4] and all(r[7] == 1 for r in act)
     assert len(seen) == 1
     assert seen[0][0] == 11 * 2            # one prefix partial + one own partial per token
 
