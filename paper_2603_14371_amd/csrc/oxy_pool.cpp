@@ -543,14 +543,15 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       tbl_words += blocks_for(px.len);
       const int32_t split = tile_split_for(c, px.len);
       const int32_t nsplit = (px.len + split - 1) / split;
-      const int32_t tile_tok = tile_tok_for(px.len);
+      const bool pairs = px.len <= 1024;    // EXPERIMENT: short prefix -> pairs on the streaming path
+      const int32_t tile_tok = pairs ? 2 : tile_tok_for(px.len);
       for (size_t t0 = 0; t0 < g.toks.size(); t0 += tile_tok) {
         const int32_t n = (int32_t)std::min<size_t>(tile_tok, g.toks.size() - t0);
         const int32_t tok_off = (int32_t)toks.size();
         toks.insert(toks.end(), g.toks.begin() + t0, g.toks.begin() + t0 + n);
         for (int32_t s = 0; s < nsplit; ++s)
           add_work(tok_off, n, tbl_off, s * split, std::min(px.len, (s + 1) * split),
-                   oxy::kNoCausal, s, oxy::PATH_TILE);
+                   oxy::kNoCausal, s, pairs ? oxy::PATH_STREAM : oxy::PATH_TILE);
       }
       for (int32_t t : g.toks) n_parts[t] = nsplit;
       for (const auto& so : g.solo) {
