@@ -371,38 +371,59 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   // outstanding loads per control-flow path, and a conditional load would make it wait for
   // everything at the next join.  A step past the end re-reads one hot 4 KiB (eight times the
   // same 16 B per thread); a missing page B re-reads page A.  Neither is ever used.
+  // kFresh only: the V part of a step in two halves, so that the loads of several steps can be
+  // issued before the first transpose waits for any of them.
+  // r[e] = dims vdim..vdim+3 of key e of this thread's chunks (keys 4gp+e, then 8+4gp+e-4).
+  typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+  auto fetch_fresh_k = [&](const int s, u32x4 (&st)[8]) {
+    const int pos0 = wi.kv_begin + 32 * s, last = wi.kv_end - 1;
+    const uint16_t* kn = (const uint16_t*)a.k_new + (size_t)row0 * kDim;
+    const int kkey = ((tid >> 5) & 1) * 8 + (tid & 7);
+    const int kdim = (tid >> 6) * 32 + ((tid >> 3) & 3) * 8;
+#pragma unroll
+    for (int pgi = 0; pgi < 2; ++pgi) {
+      const uint16_t* ksrc = kn + (size_t)min(pos0 + 16 * pgi + kkey, last) * kDim + kdim;
+      st[2 * pgi] = *(const u32x4*)ksrc;
+      st[2 * pgi + 1] = *(const u32x4*)(ksrc + 128);
+    }
+  };
+  auto fresh_v_load = [&](const int s, u32x2 (&r)[8]) {
+    const uint16_t* vn = (const uint16_t*)a.v_new + (size_t)row0 * kDim;
+    const int q = tid & 127, gp = (q >> 2) & 1, last = wi.kv_end - 1;
+    const int vpos = wi.kv_begin + 32 * s + 16 * (tid >> 7) + 4 * gp;
+    const int vdim = 16 * (q >> 3) + 4 * (q & 3);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      r[e] = *(const u32x2*)(vn + (size_t)min(vpos + (e < 4 ? e : e + 4), last) * kDim + vdim);
+  };
+  auto fresh_v_assemble = [&](const u32x2 (&r)[8], u32x4 (&st)[8]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {   // chunk j = dim vdim + j: halfword j of every key
+      u32x4 c;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t lo = r[2 * w][j >> 1], hi = r[2 * w + 1][j >> 1];
+        c[w] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+      }
+      st[4 + j] = c;
+    }
+  };
   auto fetch = [&](const int s, u32x4 (&st)[8]) {
     const bool real = s < nsteps;
     if constexpr (kFresh) {
-      // thread tid holds chunks tid and tid+256 of each page: K chunk = 8 dims of one key (one
-      // 16-byte load from the row), V chunk = one dim of 8 keys (eight 2-byte loads).  Positions
-      // at or beyond the split's end re-read its last row; they are masked like stale slots.
-      // A step past the end loads nothing here: these gathers are expensive, the rows sit in L2,
-      // and a fresh tile has few steps, so the wait that a conditional load costs is cheap.
+      // K: thread tid holds chunks tid and tid+256 of each page as everywhere (a K chunk = 8 dims
+      // of one key = one 16-byte load from the row).  V: a chunk is one dim of 8 keys, so here a
+      // thread takes FOUR NEIGHBOURING chunks (dims d..d+3, same eight keys) of ONE page: eight
+      // 8-byte loads and a 4x8 transpose in registers instead of thirty-two 2-byte gathers.
+      // Thread tid: page tid / 128, chunks 4q..4q+3 with q = tid % 128 (see commit / sanitize).
+      // Positions at or beyond the split's end re-read its last row; they are masked like stale
+      // slots.  A step past the end loads nothing: the rows sit in L2 and a fresh tile has few
+      // steps, so the wait that a conditional load costs is cheap.
       if (!real) return;
-      const int pos0 = wi.kv_begin + 32 * s, last = wi.kv_end - 1;
-      const uint16_t* kn = (const uint16_t*)a.k_new + (size_t)row0 * kDim;
-      const uint16_t* vn = (const uint16_t*)a.v_new + (size_t)row0 * kDim;
-      const int kkey = ((tid >> 5) & 1) * 8 + (tid & 7);
-      const int kdim = (tid >> 6) * 32 + ((tid >> 3) & 3) * 8;
-      const int gp = (tid >> 4) & 1, vdim = (tid >> 5) * 16 + (tid & 15);
-#pragma unroll
-      for (int pgi = 0; pgi < 2; ++pgi) {
-        const uint16_t* ksrc = kn + (size_t)min(pos0 + 16 * pgi + kkey, last) * kDim + kdim;
-        st[2 * pgi] = *(const u32x4*)ksrc;
-        st[2 * pgi + 1] = *(const u32x4*)(ksrc + 128);
-        u32x4 lo, hi;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int k0 = pos0 + 16 * pgi + (i < 2 ? 4 * gp : 8 + 4 * gp) + 2 * (i & 1);
-          const uint16_t* r0 = vn + (size_t)min(k0, last) * kDim + vdim;
-          const uint16_t* r1 = vn + (size_t)min(k0 + 1, last) * kDim + vdim;
-          lo[i] = (uint32_t)r0[0] | ((uint32_t)r1[0] << 16);
-          hi[i] = (uint32_t)r0[128] | ((uint32_t)r1[128] << 16);
-        }
-        st[4 + 2 * pgi] = lo;
-        st[5 + 2 * pgi] = hi;
-      }
+      fetch_fresh_k(s, st);
+      u32x2 r[8];
+      fresh_v_load(s, r);
+      fresh_v_assemble(r, st);
       return;
     }
     const int pi = real ? 2 * s : 0;                      // page index inside the split
@@ -428,6 +449,18 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     const int left = wi.kv_end - (wi.kv_begin + 32 * s);
     if (s < nsteps && left < 32) {
       asm volatile("" ::: "memory");
+      if constexpr (kFresh) {   // four chunks of page tid / 128, all with the same eight keys
+        const int k0 = 16 * (tid >> 7) + 4 * (((tid & 127) >> 2) & 1);
+        u32x4 mask;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          mask[i] = (k0 + 2 * i < left ? 0xffffu : 0u) | (k0 + 2 * i + 1 < left ? 0xffff0000u : 0u);
+          mask[2 + i] = (k0 + 8 + 2 * i < left ? 0xffffu : 0u) | (k0 + 9 + 2 * i < left ? 0xffff0000u : 0u);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st[4 + j] &= mask;
+        return;
+      }
       const int gp = (tid >> 4) & 1;
 #pragma unroll
       for (int pgi = 0; pgi < 2; ++pgi) {
@@ -449,6 +482,12 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     *(u32x4*)(dst + kOffKA + 4096) = st[1];
     *(u32x4*)(dst + kOffKB) = st[2];
     *(u32x4*)(dst + kOffKB + 4096) = st[3];
+    if constexpr (kFresh) {   // chunks 4q..4q+3 of page tid / 128
+      char* vd = smem + stage * kStageBytes + ((tid >> 7) ? kOffVB : kOffVA) + (tid & 127) * 64;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *(u32x4*)(vd + j * 16) = st[4 + j];
+      return;
+    }
     *(u32x4*)(dst + kOffVA) = st[4];
     *(u32x4*)(dst + kOffVA + 4096) = st[5];
     *(u32x4*)(dst + kOffVB) = st[6];
@@ -521,8 +560,22 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     }
   }
   __builtin_amdgcn_sched_barrier(0);
-  fetch(0, st0);
-  fetch(1, st1);
+  if constexpr (kFresh) {
+    // every load of steps 0 and 1 goes out before the first transpose waits for its rows
+    u32x2 r0[8], r1[8];
+    fetch_fresh_k(0, st0);
+    fresh_v_load(0, r0);
+    if (nsteps > 1) {
+      fetch_fresh_k(1, st1);
+      fresh_v_load(1, r1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    fresh_v_assemble(r0, st0);
+    if (nsteps > 1) fresh_v_assemble(r1, st1);
+  } else {
+    fetch(0, st0);
+    fetch(1, st1);
+  }
   __builtin_amdgcn_sched_barrier(0);
   sanitize(0, st0);
   commit(0, st0);
