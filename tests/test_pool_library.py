@@ -181,13 +181,11 @@ def test_work_list_of_tiny_config():
         if op.get("attend", True):
             seen.append(_check_work_list(pool, model, op, batch))
             work = B.oxy_batch_work(batch)
-            # 10 chunk tokens on a 64-token prefix: tiles of up to 4 tokens (short source) x 1
-            # split, shared pages (path 1), no causal base; the decode token streams the short
-            # prefix on its own
+            # a short (64-token) prefix is streamed (path 0), no causal base, 1 split: the decode
+            # token on its own, the 10 chunk tokens in pairs
             work = work[work[:, 7] != 2]
             prefix_items = [r for r in work if r[5] == 0x3fffffff and r[4] == 64]
-            assert sorted((int(r[1]), int(r[7])) for r in prefix_items) == [(1, 0), (2, 1), (4, 1),
-                                                                             (4, 1)]
+            assert sorted((int(r[1]), int(r[7])) for r in prefix_items) == [(1, 0)] + [(2, 0)] * 5
             # the decode query sits at own position 4, sees own keys 0..4, streams its pages
             dec = [r for r in work if r[5] != 0x3fffffff]
             assert len(dec) == 1 and dec[0][5] == 4 and (dec[0][3], dec[0][4]) == (0, 5)
