@@ -218,6 +218,19 @@ def test_stress_trace_indexes_identically_through_churn():
         n += 1
         if op.get("mixed"):
             assert B.oxy_batch_info(batch)[1] == 164
+            n_partials, _ = _check_work_list(pool, model, op, batch)
+            work = B.oxy_batch_work(batch)
+            work = work[work[:, 7] != 2]
+            # long (2048-token) prefixes: everything attached to a prefix shares tiles of up to 8
+            # tokens (8 decode streams = one tile; a 50-token chunk = 7 more), 8 splits of 256
+            prefix_items = work[(work[:, 5] == 0x3fffffff) & (work[:, 4] - work[:, 3] == 256) &
+                                (work[:, 7] == 1)]
+            assert len(prefix_items) == 8 * (8 + 2 * 7)
+            assert set(int(x) for x in prefix_items[:, 1]) == {2, 8}
+            # own histories are streamed in splits of 256
+            own = work[work[:, 5] != 0x3fffffff]
+            assert np.all(own[:, 7] == 0) and np.all(own[:, 4] - own[:, 3] <= 256)
+            assert len(work) <= 512            # all work items of a stress layer are resident at once
     assert n > 1000
 
 
