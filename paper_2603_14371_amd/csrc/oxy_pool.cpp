@@ -600,7 +600,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       const int32_t nw = (int32_t)(hdr.size() / kHdr);
       constexpr int kXcd = 8, kCuPerXcd = 32;
       struct Rec {
-        int64_t key;     // tiles: (table, split begin); streaming items: unique
+        int64_t key;     // readers of shared pages: (table, split begin); others: unique
         int32_t idx, cost;
       };
       std::vector<Rec> recs(nw);
@@ -608,10 +608,12 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         const int32_t* r = &hdr[(size_t)i * kHdr];
         const int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
         const bool tile = (r[oxy::W_PATH] & oxy::kPathMask) == oxy::PATH_TILE;
+        // work items that read pages others read too: tiles, and streaming items on prefix pages
+        const bool shares = tile || !(r[oxy::W_PATH] & oxy::kPathAppends);
         recs[i].idx = i;
         recs[i].cost = tile ? 2 * steps : steps;
-        recs[i].key = tile ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
-                           : -(int64_t)i - 1;
+        recs[i].key = shares ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
+                             : -(int64_t)i - 1;
       }
       std::stable_sort(recs.begin(), recs.end(),
                        [](const Rec& a, const Rec& b) { return a.key < b.key; });
