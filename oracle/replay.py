@@ -57,8 +57,10 @@ class OracleWorld:
                 old = self.prefix_kv[pid].get(layer)
                 if old is None:
                     old = (np.zeros((0, k.shape[1]), np.uint16),) * 2
-                self.prefix_kv[pid][layer] = (
-                    np.concatenate([old[0][:pos0], k]), np.concatenate([old[1][:pos0], v]))
+                # tokens [pos0, pos0+n) are (over)written, everything else stays: the
+                # logical length is max(old length, pos0+n), as in the pool model
+                self.prefix_kv[pid][layer] = tuple(
+                    np.concatenate([o[:pos0], new, o[pos0 + n:]]) for o, new in zip(old, (k, v)))
             return {"slots": slots}
         if kind == "prefix_fork":
             pid = self.pool.prefix_fork(op["parent"], op["n"])

@@ -3,7 +3,7 @@ prefix == isolated per-task copies, the action expert's view never sees language
 batch independence, frame-chop invariance, placement independence.  No GPU."""
 import numpy as np
 
-from oracle import attention
+from oracle import attention, brute
 from oracle.pool_model import ACTION, DECODE
 from oracle.replay import OracleWorld
 from paper_2603_14371_amd import synth
@@ -162,3 +162,103 @@ def test_forked_prefix_reads_like_an_unforked_copy():
             assert ow.pool.ref[ow.pool.prefixes[0].blocks[0]] == 4   # two handles, two streams
     assert np.array_equal(outs[0]["O"][0], outs[1]["O"][0])
     assert np.array_equal(outs[0]["LSE"][0], outs[1]["LSE"][0])
+
+
+# ---- pins of the replay's bookkeeping against hand-built key/value lists ----------------
+# Expected values come from the pure-Python loops in oracle.brute on lists assembled here
+# by hand, never from the replay itself, so a slip in the replay's handling of an operation
+# (a chunk that accumulates, a rewind that keeps its tail, an overwrite that truncates or
+# misplaces) shows up as a disagreement.
+def _loops(kind, q, kp, vp, ko, vo, scale):
+    o, lse = brute.attend_item_loops(kind, q.tolist(), kp.tolist(), vp.tolist(), ko.tolist(),
+                                     vo.tolist(), scale)
+    return np.array(o), np.array(lse)
+
+
+def _tiny_source():
+    return synth.DataSource(4242, n_heads=2, head_dim=16)
+
+
+def test_action_chunk_kv_is_transient_per_denoise_step():
+    """App. A.1 Eq. 6 and Sec. 1 (heterogeneous KV semantics): the action expert reads the
+    prefill cache as read-only context over its S denoising steps and generates the chunk
+    jointly, so at every step the chunk queries see the prefix plus THAT step's chunk
+    tokens only; nothing of an earlier denoising step remains visible."""
+    data = _tiny_source()
+    w = OracleWorld(32, 1, data, 0.3)
+    pre = {"tag": 1, "tok0": 0, "n_total": 9}
+    w.apply({"op": "prefix_create"})
+    w.apply({"op": "prefix_append", "pid": 0, "n": 9, "pos0": 0, "data": pre})
+    a = w.apply({"op": "stream_create", "pid": 0, "kind": ACTION})["sid"]
+    kp, vp = data(pre, 0, "k", 9), data(pre, 0, "v", 9)
+    blocks = None
+    for s in range(4):
+        rec = {"tag": 10 + s, "tok0": 0, "n_total": 5}
+        got = w.apply({"op": "step", "items": [(a, 5)], "data": rec})
+        exp_o, exp_lse = _loops(ACTION, data(rec, 0, "q", 5), kp, vp, data(rec, 0, "k", 5),
+                                data(rec, 0, "v", 5), 0.3)
+        np.testing.assert_allclose(got["O"][0], exp_o, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(got["LSE"][0], exp_lse, rtol=1e-12, atol=1e-13)
+        # the un-paged truth holds exactly this step's five rows, in the same blocks
+        assert np.array_equal(w.stream_kv[a][0][0], data(rec, 0, "k", 5))
+        assert w.pool.streams[a].length == 5
+        assert blocks in (None, list(w.pool.streams[a].blocks))
+        blocks = list(w.pool.streams[a].blocks)
+
+
+def test_rewind_drops_the_tail_and_later_tokens_take_its_place():
+    """Sec. 3.2 (compatibility with parallel decoding: rejected draft tokens are rolled
+    back): decode 6 tokens, rewind to 3, append 2 new ones -> the new queries see the
+    prefix, the first three original tokens and the two new ones, nothing of the dropped
+    three."""
+    data = _tiny_source()
+    w = OracleWorld(32, 1, data, 0.3)
+    pre = {"tag": 1, "tok0": 0, "n_total": 7}
+    first = {"tag": 2, "tok0": 0, "n_total": 6}
+    second = {"tag": 3, "tok0": 0, "n_total": 2}
+    w.apply({"op": "prefix_create"})
+    w.apply({"op": "prefix_append", "pid": 0, "n": 7, "pos0": 0, "data": pre})
+    d = w.apply({"op": "stream_create", "pid": 0, "kind": DECODE})["sid"]
+    w.apply({"op": "step", "items": [(d, 6)], "data": first, "attend": False})
+    slots_before = list(w.pool.streams[d].blocks)
+    w.apply({"op": "stream_rewind", "sid": d, "len": 3})
+    got = w.apply({"op": "step", "items": [(d, 2)], "data": second})
+    ko = np.concatenate([data(first, 0, "k", 6)[:3], data(second, 0, "k", 2)])
+    vo = np.concatenate([data(first, 0, "v", 6)[:3], data(second, 0, "v", 2)])
+    exp_o, exp_lse = _loops(DECODE, data(second, 0, "q", 2), data(pre, 0, "k", 7),
+                            data(pre, 0, "v", 7), ko, vo, 0.3)
+    np.testing.assert_allclose(got["O"][0], exp_o, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(got["LSE"][0], exp_lse, rtol=1e-12, atol=1e-13)
+    # positions 3 and 4 of the same block are written again; no block moved or was freed
+    blk = slots_before[0]
+    assert got["slots"] == [blk * 16 + 3, blk * 16 + 4]
+    assert w.pool.streams[d].length == 5 and w.pool.streams[d].blocks == slots_before
+
+
+def test_prefix_append_below_the_length_overwrites_in_place():
+    """An append at pos0 < len on a prefix that nobody has attached to yet rewrites tokens
+    [pos0, pos0+n) and leaves every other token alone; the length only grows."""
+    data = _tiny_source()
+    w = OracleWorld(32, 1, data, 0.3)
+    a_rec = {"tag": 1, "tok0": 0, "n_total": 20}
+    b_rec = {"tag": 2, "tok0": 0, "n_total": 4}
+    c_rec = {"tag": 3, "tok0": 0, "n_total": 8}
+    w.apply({"op": "prefix_create"})
+    s_a = w.apply({"op": "prefix_append", "pid": 0, "n": 20, "pos0": 0, "data": a_rec})["slots"]
+    s_b = w.apply({"op": "prefix_append", "pid": 0, "n": 4, "pos0": 12, "data": b_rec})["slots"]
+    assert s_b == s_a[12:16] and w.pool.prefixes[0].length == 20      # in the middle
+    s_c = w.apply({"op": "prefix_append", "pid": 0, "n": 8, "pos0": 18, "data": c_rec})["slots"]
+    assert s_c[:2] == s_a[18:20] and w.pool.prefixes[0].length == 26  # across the old end
+    d = w.apply({"op": "stream_create", "pid": 0, "kind": DECODE})["sid"]
+    q_rec = {"tag": 4, "tok0": 0, "n_total": 1}
+    got = w.apply({"op": "step", "items": [(d, 1)], "data": q_rec})
+    parts = lambda what: np.concatenate([data(a_rec, 0, what, 20)[:12], data(b_rec, 0, what, 4),
+                                         data(a_rec, 0, what, 20)[16:18],
+                                         data(c_rec, 0, what, 8)])
+    kp, vp = parts("k"), parts("v")
+    assert len(kp) == 26
+    exp_o, exp_lse = _loops(DECODE, data(q_rec, 0, "q", 1), kp, vp, data(q_rec, 0, "k", 1),
+                            data(q_rec, 0, "v", 1), 0.3)
+    np.testing.assert_allclose(got["O"][0], exp_o, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(got["LSE"][0], exp_lse, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(w.prefix_kv[0][0][0], kp)
