@@ -547,7 +547,7 @@ def stream_probe(device, n_bytes, layers=18, reps=5):
     launch as one attention launch (cycling over `layers` distinct regions so that nothing sits
     in the memory-side cache), and for a launch four times as large."""
     import torch
-    from paper_2603_14371_amd import binding as B
+    from paper_2603_14371_amd import benchaid
     out = {}
     stream = torch.cuda.current_stream(device).cuda_stream
     sink = torch.zeros(64, dtype=torch.uint8, device=device)
@@ -561,7 +561,7 @@ def stream_probe(device, n_bytes, layers=18, reps=5):
             for l in range(layers):
                 a, b = ev[r * layers + l]
                 a.record()
-                B.oxy_read_probe(buf.data_ptr() + l * nb, nb, sink.data_ptr(), stream)
+                benchaid.read(buf.data_ptr() + l * nb, nb, sink.data_ptr(), stream)
                 b.record()
         torch.cuda.synchronize(device)
         us = [a.elapsed_time(b) * 1e3 for a, b in ev[layers:]]
@@ -574,13 +574,13 @@ def stream_probe(device, n_bytes, layers=18, reps=5):
 def pmc_probe(device, reps=3, mib=256):
     """Plain copies of known size, so that traffic counters can be calibrated in the same run."""
     import torch
-    from paper_2603_14371_amd import binding as B
+    from paper_2603_14371_amd import benchaid
     n = mib << 20
     src = torch.empty(n, dtype=torch.uint8, device=device).fill_(1)
     dst = torch.empty(n, dtype=torch.uint8, device=device)
     stream = torch.cuda.current_stream(device).cuda_stream
     for _ in range(reps):
-        B.oxy_copy_probe(dst.data_ptr(), src.data_ptr(), n, stream)
+        benchaid.copy(dst.data_ptr(), src.data_ptr(), n, stream)
     torch.cuda.synchronize(device)
     return n
 

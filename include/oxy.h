@@ -26,13 +26,19 @@
  *  - Every call returns 0 (OXY_OK) or a negative oxy_status; no C++ exception
  *    crosses this boundary.  oxy_last_error() gives a thread-local message.
  *  - A failing call changes no pool state (OXY_ERR_NO_BLOCKS is detected before
- *    any block is taken).
+ *    any block is taken; a HIP launch or copy that fails inside oxy_prefix_append
+ *    or oxy_batch_build gives its blocks and lengths back before returning).
  *  - Pointers marked DEVICE are device memory owned by the caller; pointers
  *    marked HOST are host memory owned by the caller.  The library owns only its
  *    host metadata and a small pinned staging buffer per live batch.
  *  - All device work is enqueued on the caller's hipStream_t (passed as void*);
  *    no call synchronises the device.  Calls that touch the same batch, or that
  *    free and re-use blocks, must be ordered on one HIP stream by the caller.
+ *    A batch's descriptor and split results live in one of max_live_batches
+ *    workspace slots, and oxy_batch_destroy hands the slot to the next
+ *    oxy_batch_build at once, without waiting for the device: drive all batches of
+ *    a pool on ONE HIP stream (then stream order protects the slot), or order the
+ *    next build's stream behind the destroyed batch's last launch yourself.
  *  - Ids are sequential from 0 and never reused (App. A.2: the id of a request
  *    is the number of requests created before it); prefixes and streams count
  *    separately.
@@ -110,9 +116,12 @@ typedef struct {
   int32_t max_append_tokens;/* new tokens per batch, append-only ones included (0 -> 16*num_blocks) */
   int32_t max_work_items;   /* attention work items per batch (0 -> 16384)                   */
   int32_t max_partials;     /* per-token split results per batch (0 -> 32*max_q_tokens)      */
-  int32_t split_tokens;     /* KV tokens per work item of the shared-tile path (prefix phase, action
-                               chunks), multiple of 32, <= 1024.  0 -> chosen from the length of
-                               the KV source alone: about an eighth of it, within [64, 256]      */
+  int32_t split_tokens;     /* KV tokens per work item wherever query tokens share KV pages: the
+                               prefix phase (tiles of 8 tokens on a prefix longer than 1024
+                               tokens, streamed token pairs on a shorter one) and the own phase of
+                               action chunks and multi-token decode.  Multiple of 32, <= 1024.
+                               0 -> chosen from the length of the KV source alone: about an
+                               eighth of it, within [64, 256]                                */
   int32_t stream_split_tokens; /* KV tokens per work item of the decode streaming path, multiple
                                of 32, <= 1024 (0 -> split_tokens, or 256 if that is 0).  Both depend
                                only on the pool and the item, so an item's arithmetic never
@@ -242,17 +251,6 @@ int32_t oxy_batch_slots(const oxy_batch *batch, int64_t *out, int32_t cap);
 /* Raw work list, 8 int32 per item: token-list offset, token count, block-table offset,
  * kv_begin, kv_end, causal base position (or 0x3fffffff), partial index, path. */
 int32_t oxy_batch_work(const oxy_batch *batch, int32_t *out, int32_t cap_items);
-
-/* Measurement aid: a plain 16-byte-per-lane device copy of `bytes` (multiple of 16) from src to
- * dst (both DEVICE), enqueued on hip_stream.  It moves a known number of bytes, so hardware
- * traffic counters read during it calibrate the same counters read during the attention launch. */
-int32_t oxy_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
-/* Measurement aid: a read-only streaming pass over `bytes` (multiple of 32 KiB) of src (DEVICE):
- * every wavefront pulls two 16 KiB blocks with all its loads in flight and folds them into a
- * value it never stores (sink, DEVICE, >= 16 bytes, is written only in a case that cannot occur).
- * Timed next to the attention launch it gives the rate a plain streaming kernel reaches on this
- * machine for the same number of bytes per launch. */
-int32_t oxy_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
 
 /* --- frame scheduler: the per-frame execution flow (Alg. 1, App. A.3; Sec. 3.2) --------
  * Host logic only.  Per frame: the caller appends the prefill KV of each new observation to a

@@ -33,7 +33,7 @@ EXPORTS = [
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
     "oxy_block_refcounts", "oxy_free_blocks", "oxy_pool_stats", "oxy_batch_info",
-    "oxy_batch_slots", "oxy_batch_work", "oxy_copy_probe", "oxy_read_probe",
+    "oxy_batch_slots", "oxy_batch_work",
     "oxy_sched_create", "oxy_sched_destroy", "oxy_sched_admit", "oxy_sched_next_step",
     "oxy_sched_end_frame", "oxy_sched_info", "oxy_sched_request_info", "oxy_sched_calibrate",
 ]
@@ -116,8 +116,6 @@ def lib():
             "oxy_batch_info": [vp, pi32, pi32, pi32, pi32],
             "oxy_batch_slots": [vp, ctypes.POINTER(ctypes.c_int64), i32],
             "oxy_batch_work": [vp, pi32, i32],
-            "oxy_copy_probe": [vp, vp, ctypes.c_size_t, vp],
-            "oxy_read_probe": [vp, ctypes.c_size_t, vp, vp],
             "oxy_sched_create": [vp, ctypes.POINTER(SchedConfig), ctypes.POINTER(vp)],
             "oxy_sched_destroy": [vp],
             "oxy_sched_admit": [vp, i32, i32, pi32],
@@ -348,15 +346,6 @@ def oxy_batch_work(batch):
     return out[:n]
 
 
-def oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream):
-    _check(lib().oxy_copy_probe(dst_ptr, src_ptr, n_bytes, stream or None))
-
-
-def oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream):
-    _check(lib().oxy_read_probe(src_ptr, n_bytes, sink_ptr, stream or None))
-
-
-# ---- frame scheduler -------------------------------------------------------------------
 def oxy_sched_create(pool, k, denoise_steps, chunk, max_active=0, mode=SCHED_BATCHED):
     cfg = SchedConfig(k, denoise_steps, chunk, max_active, mode)
     out = ctypes.c_void_p()

@@ -11,11 +11,15 @@ SOURCES = ["oxy_kernels.hip", "oxy_pool.cpp", "oxy_sched.cpp"]
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose=False):
+PROBE_SRC = os.path.join(HERE, "benchaid", "probe_kernels.hip")
+PROBE_LIB = os.path.join(HERE, "benchaid", "libprobe.so")
+
+
+def _hipcc(sources, target, verbose):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-result"]
     cmd += DEVICE_FLAGS
-    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    cmd += list(sources) + ["-o", target]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -25,6 +29,13 @@ def build_library(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    return target
+
+
+def build_library(verbose=False):
+    """liboxy.so (the method) and benchaid/libprobe.so (the benchmark's measurement aids)."""
+    _hipcc([os.path.join(CSRC, s) for s in SOURCES], LIB, verbose)
+    _hipcc([PROBE_SRC], PROBE_LIB, verbose)
     return LIB
 
 

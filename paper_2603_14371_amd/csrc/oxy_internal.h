@@ -83,7 +83,5 @@ struct AppendArgs {
 // merge of `a`, and in the same launch the append described by `next` (may be null)
 hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s,
                                hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
-hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s);
-hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s);
 
 }  // namespace oxy

@@ -242,16 +242,6 @@ constexpr int kSmemBytes = 4 * 16 * kMergeStride * 4; // 66560 >= 2 * kStageByte
 static_assert(2 * kStageBytes <= kSmemBytes, "two stages must fit");
 constexpr float kGrow = 8.f;  // the reference max only moves when a logit exceeds it by 2^8
 
-// Timeline probes, compiled in only with -DOXY_DEBUG_PROBES (never in the shipped library):
-// thread 0 of every workgroup leaves wall-clock marks at fixed points of its path, plus its
-// path, step count, XCD and hardware id; oxy_debug_read copies them out.
-#ifdef OXY_DEBUG_PROBES
-__device__ unsigned long long g_dbg[16384 * 16];
-#define DBG_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) g_dbg[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define DBG_MARK(i) do { } while (0)
-#endif
-
 // One 32-key step of the online softmax for the 16 rows of a wavefront.  s0/s1 hold the raw
 // dot products of this lane's row with keys pos + 16(g/2) + 8hf + 4(g%2) + e (hf = 0 / 1).
 // m is the reference max of the row in the scaled log2 domain.  It only moves when a logit
@@ -519,20 +509,14 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   // flight.  The scheduling barriers keep the order "issue s+2, compute s, then wait for s+1",
   // otherwise the wait would be hoisted above the compute.
   auto body = [&](const int s, u32x4 (&cur)[8], u32x4 (&nxt)[8]) {
-    if (s == 3) DBG_MARK(8);
     fetch(s + 2, cur);
     __builtin_amdgcn_sched_barrier(0);
-    if (s == 3) DBG_MARK(9);
     if (wave_active && s < nsteps) compute(s);
     __builtin_amdgcn_sched_barrier(0);
-    if (s == 3) DBG_MARK(10);
     sanitize(s + 1, nxt);
     commit((s + 1) & 1, nxt);
-    if (s == 3) DBG_MARK(11);
     __syncthreads();
-    if (s == 3) DBG_MARK(12);
   };
-  DBG_MARK(1);
   // kFresh: the pool still has to receive the rows; the tile of split 0 writes its own query
   // tokens'.  All eight rows are loaded first (the record repeats the last token id for a
   // short tile), the stores follow once the first pages have been waited for anyway.
@@ -587,12 +571,10 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     }
   }
   __syncthreads();
-  DBG_MARK(2);
   for (int s = 0; s < nsteps; s += 2) {   // steps in pairs; a step past the end moves dummies
     body(s, st0, st1);
     body(s + 1, st1, st0);
   }
-  DBG_MARK(3);
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   // The partial leaves as (m, l, scale, acc / scale in fp16): half the bytes of fp32, and the
@@ -680,7 +662,6 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
 #pragma unroll
     for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * 512);
   };
-  DBG_MARK(1);
   // Folded append: the query tokens of a streaming item are its new rows.  Those inside this
   // split's key range are written to the pool by this workgroup (no other workgroup reads
   // them in this launch), and a workgroup barrier orders the writes before the page loads that
@@ -750,7 +731,6 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     u32x4 pf, pl;
     softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
                  pf, pl);
-    if (s == wv) DBG_MARK(8);
     __builtin_amdgcn_sched_barrier(0);  // the next K pages reuse kr[]: issue only after S
     load_k(s + 4);
     __builtin_amdgcn_sched_barrier(0);
@@ -762,14 +742,12 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     }
 #pragma unroll
     for (int c = 0; c < 16; ++c) acc[c] = mfma16(vr[c], pl, mfma16(vr[c], pf, acc[c]));
-    if (s == wv) DBG_MARK(9);
     __builtin_amdgcn_sched_barrier(0);  // likewise vr[]
     load_v(s + 4);
     __builtin_amdgcn_sched_barrier(0);
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  DBG_MARK(3);
   // combine the four wavefronts' results (log-sum-exp rule) and write one partial
   float* sm = (float*)smem;
 #pragma unroll
@@ -841,7 +819,6 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   wi.part_idx = __builtin_amdgcn_readlane(wi.rec, W_PART_IDX);
   const int path_word = __builtin_amdgcn_readlane(wi.rec, W_PATH);
   const int path = path_word & kPathMask;
-  DBG_MARK(0);
   if (path == PATH_TILE) {
     __builtin_amdgcn_s_setprio(2);   // compute-heavy: issue ahead of co-resident streaming waves
     if (a.k_new && (path_word & kPathFresh))
@@ -853,22 +830,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   } else {
     return;   // padding record
   }
-  DBG_MARK(4);
-#ifdef OXY_DEBUG_PROBES
-  if (threadIdx.x == 0 && blockIdx.x < 16384) {
-    g_dbg[blockIdx.x * 16 + 5] = path;
-    g_dbg[blockIdx.x * 16 + 6] = (wi.kv_end - wi.kv_begin + 31) >> 5;
-    g_dbg[blockIdx.x * 16 + 7] = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);  // XCC_ID
-    g_dbg[blockIdx.x * 16 + 14] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);  // HW_ID
-  }
-#endif
 }
-
-#ifdef OXY_DEBUG_PROBES
-extern "C" int oxy_debug_read(unsigned long long* out, int n_words) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg), (size_t)n_words * 8);
-}
-#endif
 
 // ------------------------------------------------------------------------------------------
 // merge of a query token's partials (log-sum-exp rule).  One workgroup per token; a thread owns
@@ -981,44 +943,6 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   hipError_t e = launch_attention_work(a, s);
   if (e != hipSuccess) return e;
   return launch_merge_append(a, nullptr, s);
-}
-
-// plain copy of known size (calibration of traffic counters)
-__global__ __launch_bounds__(256) void copy_probe_kernel(u32x4* __restrict__ dst,
-                                                         const u32x4* __restrict__ src, size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
-    dst[i] = src[i];
-}
-
-hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s) {
-  const size_t n16 = bytes / 16;
-  if (n16 == 0) return hipSuccess;
-  const size_t want = (n16 + 255) / 256;
-  copy_probe_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>((u32x4*)dst, (const u32x4*)src, n16);
-  return hipGetLastError();
-}
-
-// read-only streaming pass: one wavefront per 32 KiB, all 32 loads in flight
-__global__ __launch_bounds__(256, 2) void read_probe_kernel(const char* __restrict__ src,
-                                                            u32x4* __restrict__ sink) {
-  const int lane = threadIdx.x & 63;
-  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const char* p = src + wave * 32768 + lane * 16;
-  u32x4 v[32];
-#pragma unroll
-  for (int i = 0; i < 32; ++i) v[i] = *(const u32x4*)(p + i * 1024);
-  u32x4 acc = {0, 0, 0, 0};
-#pragma unroll
-  for (int i = 0; i < 32; ++i) acc ^= v[i];
-  if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0xf39cc060u && acc[3] == 0x5cedc834u)
-    sink[0] = acc;   // keeps the loads alive; practically never taken
-}
-
-hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t s) {
-  const size_t n = bytes / (4 * 32768);
-  if (n == 0) return hipSuccess;
-  read_probe_kernel<<<(unsigned)n, 256, 0, s>>>((const char*)src, (u32x4*)sink);
-  return hipGetLastError();
 }
 
 }  // namespace oxy

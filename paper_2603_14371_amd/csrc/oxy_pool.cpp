@@ -123,9 +123,14 @@ bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
   return true;
 }
 
+// Capacity of a batch's flat block tables.  Every block sits in one table, except blocks
+// shared by forked prefixes, which every such prefix lists: twice the pool covers one fork
+// level of everything.
+size_t table_words_of(const oxy_pool_config& c) { return 2 * (size_t)c.num_blocks; }
+
 size_t desc_words_of(const oxy_pool_config& c) {
   return (size_t)c.max_append_tokens + (size_t)oxy::kWorkWords * c.max_work_items +
-         2 * (size_t)c.max_q_tokens /* token lists */ + (size_t)c.num_blocks /* tables */ +
+         2 * (size_t)c.max_q_tokens /* token lists */ + table_words_of(c) /* tables */ +
          2 * (size_t)c.max_q_tokens /* part_off, n_parts */;
 }
 
@@ -300,6 +305,8 @@ int32_t prefix_append_impl(oxy_pool* p, int32_t pid, int32_t layer_begin, int32_
   int32_t need = blocks_for(pos0 + n_tokens) - (int32_t)px.blocks.size();
   if (need > (int32_t)p->free_stack.size())
     return fail(OXY_ERR_NO_BLOCKS, "%s: need %d blocks, %zu free", who, need, p->free_stack.size());
+  const size_t old_blocks = px.blocks.size();
+  const int32_t old_len = px.len;
   for (int32_t i = 0; i < need; ++i) {
     int32_t b = p->free_stack.back();
     p->free_stack.pop_back();
@@ -308,6 +315,16 @@ int32_t prefix_append_impl(oxy_pool* p, int32_t pid, int32_t layer_begin, int32_
   }
   px.len = std::max(px.len, pos0 + n_tokens);
   if (p->host_only) return OXY_OK;
+  // a launch that fails leaves the pool as it was: the blocks go back in reverse order of
+  // their pops, which restores the free stack exactly
+  auto roll_back = [&]() {
+    while (px.blocks.size() > old_blocks) {
+      p->ref[px.blocks.back()] = 0;
+      p->free_stack.push_back(px.blocks.back());
+      px.blocks.pop_back();
+    }
+    px.len = old_len;
+  };
   // device copy, at most kMaxInlineBlocks blocks per launch (block ids travel by value)
   const char* kp = (const char*)k;
   const char* vp = (const char*)v;
@@ -325,7 +342,10 @@ int32_t prefix_append_impl(oxy_pool* p, int32_t pid, int32_t layer_begin, int32_
         kp + (size_t)done * oxy::kDim * 2, vp + (size_t)done * oxy::kDim * 2, ids,
         pos - first_block * kPage, n, layer_base(p, layer_begin), layer_end - layer_begin,
         src_layer_stride, pool_layer_stride, (hipStream_t)hip_stream);
-    if (e != hipSuccess) return hip_fail(e, "prefix_append: launch");
+    if (e != hipSuccess) {
+      roll_back();
+      return hip_fail(e, "prefix_append: launch");
+    }
     done += n;
   }
   return OXY_OK;
@@ -437,6 +457,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   struct Plan {
     Stream* s;
     int32_t old_len, new_len, need, tok0;
+    int32_t len_before;   // the stream's length when the call began (an ACTION item is rewound)
   };
   std::vector<Plan> plan;
   plan.reserve(n_items);
@@ -456,7 +477,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
     if (new_len > (int64_t)kPage * c.num_blocks)
       return fail(OXY_ERR_NO_BLOCKS, "batch_build: stream %d would exceed the pool", items[i].stream_id);
     int32_t need = std::max(0, blocks_for((int32_t)new_len) - (int32_t)s.blocks.size());
-    plan.push_back({&s, old_len, (int32_t)new_len, need, (int32_t)n_tokens});
+    plan.push_back({&s, old_len, (int32_t)new_len, need, (int32_t)n_tokens, s.len});
     need_total += need;
     n_tokens += items[i].n_new;
   }
@@ -492,20 +513,22 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       const int32_t w[kHdr] = {tok_off, n_tok, tbl_off, b, e, q0, part, path};
       hdr.insert(hdr.end(), w, w + kHdr);
     };
-    // Which path evaluates a query depends on its item only (kind, n_new, phase), never on its
-    // batch mates, so an item's arithmetic is the same in every batch it can appear in:
-    //   prefix phase -> tiles of up to 8 tokens sharing the prefix pages through LDS;
-    //   own phase    -> items with <= 2 new tokens (decode) stream their own pages;
-    //                   larger items (action chunks, multi-token decode) use tiles of 8.
-    // Tokens per tile: 8 (64 MFMA rows, all four wavefronts) on long KV sources, where what
-    // counts is reading the pages once for as many queries as possible; 4 (two wavefronts
-    // compute, all four move pages) on short ones, where few workgroups exist anyway and a
-    // step is bound by the tile's own LDS reads and arithmetic.
+    // Which path evaluates a query depends on its item and its prefix only (kind, n_new, phase,
+    // prefix length), never on its batch mates, so an item's arithmetic is the same in every
+    // batch it can appear in:
+    //   prefix phase, prefix longer than kStreamPrefixMax -> all queries attached to the prefix
+    //                   share tiles of 8 tokens (64 MFMA rows), which fetch the prefix pages once
+    //                   for all of them;
+    //   prefix phase, shorter prefix -> streaming path: a decode item (<= 2 new tokens) on its
+    //                   own, the other queries (an action chunk) two tokens at a time.  With a
+    //                   short prefix the launch is bound by latency, CUs are idle, and the
+    //                   re-reads hit L2; four steps in flight per workgroup beat a tile's two;
+    //   own phase    -> items with <= 2 new tokens (decode) stream their own pages; larger
+    //                   items (action chunks, multi-token decode) use tiles: 8 tokens on a long
+    //                   KV source, 4 (two wavefronts compute, all four move pages) on one of at
+    //                   most 1024 tokens, where few workgroups exist anyway and a step is
+    //                   bound by the tile's own LDS reads and arithmetic.
     auto tile_tok_for = [](int32_t source_len) { return source_len <= 1024 ? 4 : 8; };
-    // A decode item (<= 2 new tokens) on a short prefix streams the prefix pages on its own,
-    // like its own pages: four steps in flight at once instead of a tile's two, and with few
-    // queries per prefix there is little to share.  On a long prefix it joins the tiles, which
-    // fetch the prefix once for all queries attached to it.
     constexpr int32_t kStreamPrefixMax = 1024;
     struct Group {
       int32_t pid;
@@ -543,7 +566,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       tbl_words += blocks_for(px.len);
       const int32_t split = tile_split_for(c, px.len);
       const int32_t nsplit = (px.len + split - 1) / split;
-      const bool pairs = px.len <= 1024;    // EXPERIMENT: short prefix -> pairs on the streaming path
+      const bool pairs = px.len <= kStreamPrefixMax;   // short prefix: pairs on the streaming path
       const int32_t tile_tok = pairs ? 2 : tile_tok_for(px.len);
       for (size_t t0 = 0; t0 < g.toks.size(); t0 += tile_tok) {
         const int32_t n = (int32_t)std::min<size_t>(tile_tok, g.toks.size() - t0);
@@ -691,7 +714,10 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   if (n_partials > c.max_partials)
     return fail(OXY_ERR_WORKSPACE, "batch_build: %lld partials > max_partials %d",
                 (long long)n_partials, c.max_partials);
-  if (tbl_words > c.num_blocks) return fail(OXY_ERR_WORKSPACE, "batch_build: block tables too long");
+  if ((size_t)tbl_words > table_words_of(c))
+    return fail(OXY_ERR_WORKSPACE,
+                "batch_build: the block tables of this batch list %d entries > %zu (forked "
+                "prefixes list shared blocks once each)", tbl_words, table_words_of(c));
 
   // ---- a free descriptor slot
   int32_t slot = -1;
@@ -777,6 +803,16 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
                                   (hipStream_t)hip_stream);
     if (e == hipSuccess) e = hipEventRecord(ds.uploaded, (hipStream_t)hip_stream);
     if (e != hipSuccess) {
+      // a failing call changes no pool state: lengths back, blocks back in reverse order of
+      // their pops (which restores the free stack exactly)
+      for (auto it = plan.rbegin(); it != plan.rend(); ++it) {
+        for (int32_t i = 0; i < it->need; ++i) {
+          p->ref[it->s->blocks.back()] = 0;
+          p->free_stack.push_back(it->s->blocks.back());
+          it->s->blocks.pop_back();
+        }
+        it->s->len = it->len_before;
+      }
       delete b;
       return hip_fail(e, "batch_build: descriptor upload");
     }
@@ -945,21 +981,6 @@ int32_t oxy_gather_kv(oxy_pool* p, int32_t layer, const int64_t* slots, int32_t 
                                              (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "gather_kv: launch");
   }
-  return OXY_OK;
-}
-
-int32_t oxy_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream) {
-  if (!dst || !src || (bytes & 15)) return fail(OXY_ERR_INVALID_ARG, "copy_probe: null or bytes % 16");
-  hipError_t e = oxy::launch_copy_probe(dst, src, bytes, (hipStream_t)hip_stream);
-  if (e != hipSuccess) return hip_fail(e, "copy_probe: launch");
-  return OXY_OK;
-}
-
-int32_t oxy_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
-  if (!src || !sink || bytes == 0 || (bytes % (4 * 32768)))
-    return fail(OXY_ERR_INVALID_ARG, "read_probe: null or bytes not a multiple of 128 KiB");
-  hipError_t e = oxy::launch_read_probe(src, bytes, sink, (hipStream_t)hip_stream);
-  if (e != hipSuccess) return hip_fail(e, "read_probe: launch");
   return OXY_OK;
 }
 
