@@ -196,6 +196,20 @@ int32_t oxy_stream_append(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
 int32_t oxy_mixed_attention(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
                             const void *q, void *out, float *lse, float scale,
                             void *hip_stream);
+/* oxy_mixed_attention for callers that cannot allocate device memory or hand a workspace of
+ * matching size to the call: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same outputs; the per-split results
+ * (un-normalised accumulators and softmax statistics, which oxy_mixed_attention keeps in the
+ * batch's workspace slot) live in a static device array inside the library instead: 2048 split
+ * results (8.25 MiB), held by every GPU the library runs on until the process ends.  The call
+ * allocates nothing and frees nothing.  OXY_ERR_WORKSPACE if the batch has more than 2048
+ * split results (oxy_batch_info: n_partials).  Every call on a GPU uses that GPU's one array:
+ * calls that overlap on one GPU (different HIP streams, or the same batch on two streams)
+ * race; calls ordered on one stream do not, and nothing in the array needs clearing between
+ * calls (every entry a launch reads was written by that launch). */
+int32_t oxy_mixed_attention_static(oxy_pool *pool, const oxy_batch *batch, int32_t layer,
+                                   const void *q, void *out, float *lse, float scale,
+                                   void *hip_stream);
 /* All layers [layer_begin, layer_end) of one step, in order: for each layer the append and
  * then the mixed attention, with the same kernels and the same effects as the two calls above
  * (this is their loop moved below the ABI: one call per step instead of two per layer).

@@ -28,7 +28,7 @@ EXPORTS = [
     "oxy_prefix_fork",
     "oxy_prefix_release",
     "oxy_stream_create", "oxy_stream_release", "oxy_stream_rewind", "oxy_batch_build",
-    "oxy_stream_append", "oxy_mixed_attention", "oxy_step_layers", "oxy_append_attention",
+    "oxy_stream_append", "oxy_mixed_attention", "oxy_mixed_attention_static", "oxy_step_layers", "oxy_append_attention",
     "oxy_batch_destroy",
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
@@ -101,6 +101,7 @@ def lib():
             "oxy_batch_build": [vp, ctypes.POINTER(Item), i32, i32, vp, ctypes.POINTER(vp)],
             "oxy_stream_append": [vp, vp, i32, vp, vp, vp],
             "oxy_mixed_attention": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
+            "oxy_mixed_attention_static": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
             "oxy_step_layers": [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp, ctypes.c_size_t,
                                 vp, ctypes.c_size_t, ctypes.c_float, i32, ctypes.POINTER(vp), vp],
             "oxy_append_attention": [vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp],
@@ -241,6 +242,11 @@ def oxy_stream_append(pool, batch, layer, k_ptr, v_ptr, stream):
 def oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr, scale, stream):
     _check(lib().oxy_mixed_attention(pool, batch, layer, q_ptr, out_ptr, lse_ptr or None,
                                      ctypes.c_float(scale), stream or None))
+
+
+def oxy_mixed_attention_static(pool, batch, layer, q_ptr, out_ptr, lse_ptr, scale, stream):
+    _check(lib().oxy_mixed_attention_static(pool, batch, layer, q_ptr, out_ptr, lse_ptr or None,
+                                            ctypes.c_float(scale), stream or None))
 
 
 def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride, q_ptr,

@@ -70,6 +70,11 @@ struct AttnArgs {
   const int32_t* d_slots;
 };
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);       // work items, then merge
+// Split-result buffers in static device memory of the current device (kStaticMaxPartials
+// entries, shared by every call on that device).  The first call on a device looks the address
+// up; later calls make no HIP call other than hipGetDevice.
+constexpr int kStaticMaxPartials = 2048;
+hipError_t static_scratch(uint16_t** part_acc, float** part_ml);
 // work items only; start/stop (may be null) receive the kernel's own begin/end timestamps
 hipError_t launch_attention_work(const AttnArgs& a, hipStream_t s, hipEvent_t start = nullptr,
                                  hipEvent_t stop = nullptr);

@@ -29,6 +29,8 @@
 
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 namespace oxy {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -937,6 +939,37 @@ hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStr
       merge_kernel<<<a.n_q, 256, 0, s>>>(a);
   }
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Split results in static device memory, for callers that cannot allocate (see
+// oxy_mixed_attention_static in oxy.h).  Every GPU the library runs on holds its own copy of
+// the array, at its own address, until the process ends; that address is looked up once per
+// device, with the device current, and is what host code passes on from then.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kStaticAccBytes = (size_t)kStaticMaxPartials * kHeads * kDim * sizeof(uint16_t);
+constexpr size_t kStaticMlBytes = (size_t)kStaticMaxPartials * kHeads * 4 * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kStaticAccBytes + kStaticMlBytes];
+
+hipError_t static_scratch(uint16_t** part_acc, float** part_ml) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    ptr_of_device[dev] = ptr;
+  }
+  *part_acc = (uint16_t*)ptr_of_device[dev];
+  *part_ml = (float*)((char*)ptr_of_device[dev] + kStaticAccBytes);
+  return hipSuccess;
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {

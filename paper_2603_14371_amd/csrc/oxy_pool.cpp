@@ -251,6 +251,16 @@ int32_t oxy_pool_create(const oxy_pool_config* cfg, oxy_pool** out) {
       s.d_base = (char*)c.workspace + (size_t)i * p->per_batch_bytes;
     }
   }
+  if (!host_only) {   // set-up of oxy_mixed_attention_static for this device, so that the call
+                      // itself never has to ask the runtime for the address
+    uint16_t* acc;
+    float* ml;
+    hipError_t e = oxy::static_scratch(&acc, &ml);
+    if (e != hipSuccess) {
+      oxy_pool_destroy(p);
+      return hip_fail(e, "pool_create: static split-result buffer");
+    }
+  }
   *out = p;
   return OXY_OK;
 }
@@ -879,6 +889,27 @@ int32_t oxy_mixed_attention(oxy_pool* p, const oxy_batch* b, int32_t layer, cons
   hipError_t e = oxy::launch_attention(attn_args(p, b, layer, q, out, lse, scale),
                                        (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e, "mixed_attention: launch");
+  return OXY_OK;
+}
+
+int32_t oxy_mixed_attention_static(oxy_pool* p, const oxy_batch* b, int32_t layer, const void* q,
+                                   void* out, float* lse, float scale, void* hip_stream) {
+  if (!p || !b || b->pool != p || !q || !out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG,
+                "mixed_attention_static: null argument, foreign batch or host-only pool");
+  if (layer < 0 || layer >= p->cfg.n_layers)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention_static: layer %d", layer);
+  if (b->flags & OXY_BATCH_APPEND_ONLY)
+    return fail(OXY_ERR_INVALID_ARG, "mixed_attention_static: batch was built append-only");
+  if (b->n_partials > oxy::kStaticMaxPartials)
+    return fail(OXY_ERR_WORKSPACE,
+                "mixed_attention_static: the batch has %d split results, the static buffer holds %d",
+                b->n_partials, oxy::kStaticMaxPartials);
+  oxy::AttnArgs a = attn_args(p, b, layer, q, out, lse, scale);
+  hipError_t e = oxy::static_scratch(&a.part_acc, &a.part_ml);
+  if (e != hipSuccess) return hip_fail(e, "mixed_attention_static: static buffer");
+  e = oxy::launch_attention(a, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "mixed_attention_static: launch");
   return OXY_OK;
 }
 
