@@ -29,7 +29,7 @@ TOKEN_BYTES = 1024          # K + V of one token in one layer: 2 * 256 * 2 B
 QO_BYTES = 2 * 8 * 256 * 2  # one query token read + one output token written
 
 
-def _build_state(workload, device, split_tokens, stream_split_tokens=0):
+def _build_state(workload, device, split_tokens, stream_split_tokens=0, max_partials=16384):
     """Replays the set-up part of a trace (everything before its first attended step) with
     random resident data; returns the world and the remaining steps."""
     import torch
@@ -37,7 +37,8 @@ def _build_state(workload, device, split_tokens, stream_split_tokens=0):
     from paper_2603_14371_amd.harness import GpuWorld
     w = workload
     gw = GpuWorld(w, None, device=device, split_tokens=split_tokens,
-                  stream_split_tokens=stream_split_tokens, want_lse=False, max_partials=16384)
+                  stream_split_tokens=stream_split_tokens, want_lse=False,
+                  max_partials=max_partials)
     gen = torch.Generator(device=device)
     gen.manual_seed(w["seed"])
     L = w["n_layers"]
@@ -137,12 +138,14 @@ def _live_kv_tokens(gw, items):
     return sum(prefixes.values()) + own
 
 
-def bench_stress(args, device):
+def bench_stress(args, device, workload=None, alt_schedules=True):
     import torch
     from paper_2603_14371_amd import synth
-    w = synth.stress(mixed_steps=args.warmup + 4 * args.steps + 2)
+    w = workload or synth.stress(mixed_steps=args.warmup + 4 * args.steps + 2)
     t0 = time.time()
-    gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens)
+    n_streams = max(len(op["items"]) for op in w["trace"] if op["op"] == "step")
+    gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens,
+                            max_partials=max(16384, 64 * n_streams))
     setup_s = time.time() - t0
     steps = [op for op in rest if op["op"] == "step"]
     items = steps[0]["items"]
@@ -175,7 +178,7 @@ def bench_stress(args, device):
     # fusion (merge l + append l+1 in one launch)
     other = {}
     for j, mode in enumerate(("separate", "fuse")):
-        if args.no_alt_schedules:
+        if args.no_alt_schedules or not alt_schedules:
             other[mode] = float("nan")
             continue
         torch.cuda.synchronize(device)
@@ -208,6 +211,37 @@ def bench_stress(args, device):
     }
     gw.close()
     return res
+
+
+def bench_sweep(args, device, counts=(64, 128, 256, 512)):
+    """The stress geometry at growing stream counts (groups of 8 streams per 2048-token prefix,
+    own histories ~U{1..2048}, two action chunks): where the work-item kernel gets to on the
+    HBM roofline as a launch grows.  The number of layers shrinks as the streams grow so that
+    every point cycles through at least ~1.5 GB of distinct KV (the memory-side cache holds
+    256 MB) without filling the card."""
+    import argparse as _ap
+    import torch
+    from paper_2603_14371_amd import synth
+    out = []
+    for n in counts:
+        layers = max(3, -(-18 * 64 // n))
+        blocks = 8192 * n // 64
+        a = _ap.Namespace(**vars(args))
+        a.steps, a.warmup = max(4, args.steps // 2), 2
+        w = synth.stress(n_layers=layers, n_streams=n, num_blocks=blocks,
+                         mixed_steps=a.warmup + 2 * a.steps + 2)
+        r = bench_stress(a, device, workload=w, alt_schedules=False)
+        out.append({"streams": n, "layers": layers,
+                    "alg_bytes_per_launch": round(r["alg_bytes_per_launch"]),
+                    "attn_launch_us": round(r["attn_launch_us"], 2),
+                    "merge_launch_us": round(r["merge_launch_us"], 2),
+                    "gbps": round(r["kv_gbps"], 1),
+                    "frac": round(r["kv_gbps"] / HBM_PEAK_GBPS, 4),
+                    "frac_with_merge": round(r["alg_bytes_per_launch"] / (
+                        (r["attn_launch_us"] + r["merge_launch_us"]) * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "step_us": round(r["step_us"], 1)})
+        torch.cuda.empty_cache()
+    return out
 
 
 def bench_frame(device, split_tokens, frames=3):
@@ -632,6 +666,10 @@ def main():
                     help="run only the arrival-pattern sweep (frames driven by the scheduler)")
     ap.add_argument("--no-alt-schedules", action="store_true",
                     help="profiling aid: skip the passes with the other launch schedules")
+    ap.add_argument("--sweep-streams", action="store_true",
+                    help="run only the stream-count sweep (64..512 streams, stress geometry)")
+    ap.add_argument("--only-stress", action="store_true",
+                    help="profiling aid: the stress section only")
     ap.add_argument("--only-frame", action="store_true",
                     help="profiling aid: run only the pi0.5-shaped frame section")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -646,6 +684,13 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     device = torch.device("cuda:0")
+    if args.sweep_streams:
+        print(json.dumps({"stream_sweep": bench_sweep(args, device)}))
+        return
+    if args.only_stress:
+        s = bench_stress(args, device)
+        print(json.dumps({k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()}))
+        return
     if args.only_frame:
         print(json.dumps({"pi05_frame": bench_frame(device, args.split_tokens)}))
         return
