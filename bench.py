@@ -87,15 +87,19 @@ class StepRunner:
         self.stream = torch.cuda.current_stream(device).cuda_stream
         self.n_tok = n_tok
 
-    def step(self, items, events=None, mode="fold"):
+    def step(self, items, events=None, mode="fold", graph=False):
         """One whole step: batch build, then append + attention for every layer (the per-layer
         loop runs below the ABI in oxy_step_layers).  mode: "fold" = the attention work items
         write the new rows themselves (two launches per layer), "separate" = append, work items,
         merge (three launches), "fuse" = the merge of layer l shares a launch with the append of
-        layer l+1 (only possible because all layers' K/V are resident here)."""
+        layer l+1 (only possible because all layers' K/V are resident here).  graph: the
+        launches of the step are recorded once per batch shape and replayed with one graph
+        launch (OXY_STEP_GRAPH)."""
         from paper_2603_14371_amd import binding as B
         gw = self.gw
         flags = {"fold": B.STEP_FOLD_APPEND, "separate": 0, "fuse": B.STEP_FUSE_ACROSS_LAYERS}[mode]
+        if graph:
+            flags |= B.STEP_GRAPH
         batch = B.oxy_batch_build(gw.pool, items, 0, self.stream)
         B.oxy_step_layers(gw.pool, batch, 0, self.L, self.k.data_ptr(), self.v.data_ptr(),
                           self.k.stride(0) * 2, self.q.data_ptr(), self.o.data_ptr(),
@@ -141,7 +145,7 @@ def _live_kv_tokens(gw, items):
 def bench_stress(args, device, workload=None, alt_schedules=True):
     import torch
     from paper_2603_14371_amd import synth
-    w = workload or synth.stress(mixed_steps=args.warmup + 4 * args.steps + 2)
+    w = workload or synth.stress(mixed_steps=2 * args.warmup + 5 * args.steps + 2)
     t0 = time.time()
     n_streams = max(len(op["items"]) for op in w["trace"] if op["op"] == "step")
     gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens,
@@ -187,6 +191,25 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
             runner.step(steps[args.warmup + (2 + j) * args.steps + i]["items"], mode=mode)
         torch.cuda.synchronize(device)
         other[mode] = (time.perf_counter() - t_start) / args.steps * 1e6
+    # ---- and the two-launch schedule recorded and replayed (one graph launch per step)
+    if args.no_alt_schedules or not alt_schedules:
+        other["fold_graph"] = float("nan")
+    else:
+        first = args.warmup + 4 * args.steps
+        for i in range(args.warmup):
+            runner.step(steps[first + i]["items"], graph=True)
+        torch.cuda.synchronize(device)
+        host_graph = []
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            h0 = time.perf_counter()
+            runner.step(steps[first + args.warmup + i]["items"], graph=True)
+            host_graph.append((time.perf_counter() - h0) * 1e6)
+        torch.cuda.synchronize(device)
+        other["fold_graph"] = (time.perf_counter() - t_start) / args.steps * 1e6
+        other["host_graph"] = float(np.mean(host_graph))
+        from paper_2603_14371_amd import binding as B
+        other["graph_stats"] = B.oxy_step_graph_stats(gw.pool)
     attn_us = [t for es in sets for t in es.work_us()]
     attn_avg_us = float(np.mean(attn_us))
     merge_avg_us = float(np.mean([t for es in sets for t in es.merge_us()]))
@@ -199,6 +222,9 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
         "step_us_with_events": step_us_ev,
         "step_us_separate": other["separate"],
         "step_us_fused": other["fuse"],
+        "step_us_graph": other["fold_graph"],
+        "graph_stats": other.get("graph_stats"),
+        "host_us_per_step_graph": other.get("host_graph", float("nan")),
         "attn_launch_us": attn_avg_us,
         "merge_launch_us": merge_avg_us,
         "alg_bytes_per_launch": alg_bytes,
@@ -244,7 +270,7 @@ def bench_sweep(args, device, counts=(64, 128, 256, 512)):
     return out
 
 
-def bench_frame(device, split_tokens, frames=3):
+def bench_frame(device, split_tokens, frames=3, graph=True):
     """pi0.5-shaped single frame (secondary figures): prefix append of 832 tokens x 18 layers,
     10 mixed steps (50-query chunk + 1 decode token), then 54 decode-only steps."""
     import torch
@@ -287,9 +313,9 @@ def bench_frame(device, split_tokens, frames=3):
                 marks["prefix"] += time.perf_counter() - t0
             elif op["op"] == "step":
                 if op["mixed"]:
-                    runner_mixed.step(op["items"])
+                    runner_mixed.step(op["items"], graph=graph)
                 else:
-                    runner_dec.step(op["items"])
+                    runner_dec.step(op["items"], graph=graph)
                 # a real decode loop needs the token of step j before step j+1: sync per step
                 torch.cuda.synchronize(device)
                 marks["mixed" if op["mixed"] else "dec"] += time.perf_counter() - t0
@@ -299,6 +325,7 @@ def bench_frame(device, split_tokens, frames=3):
             t_prefix.append(marks["prefix"])
             t_mixed.append(marks["mixed"])
             t_dec.append(marks["dec"])
+    graph_stats = B.oxy_step_graph_stats(gw.pool)
     gw.close()
     mixed_us = float(np.mean(t_mixed)) / 10 * 1e6
     dec_us = float(np.mean(t_dec)) / 54 * 1e6
@@ -311,7 +338,18 @@ def bench_frame(device, split_tokens, frames=3):
         "actions_per_s": 50.0 / t_action,
         "decode_tokens_per_s_mixed": 1.0 / (mixed_us * 1e-6),
         "decode_tokens_per_s_decode_only": 1.0 / (dec_us * 1e-6),
+        "launches": "one recorded graph per step" if graph else "two per layer from the host",
+        "graph_instantiated_updated_replayed": list(graph_stats),
     }
+
+
+def _frame_both(device, split_tokens):
+    """The pi0.5 frame with two launches per layer issued from the host and, beside it, with
+    every step replayed from its recording (one graph launch per step)."""
+    rnd = lambda d: {k: (round(v, 2) if isinstance(v, float) else v) for k, v in d.items()}
+    out = rnd(bench_frame(device, split_tokens, graph=False))
+    out["recorded_graph"] = rnd(bench_frame(device, split_tokens, graph=True))
+    return out
 
 
 def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
@@ -692,7 +730,7 @@ def main():
         print(json.dumps({k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()}))
         return
     if args.only_frame:
-        print(json.dumps({"pi05_frame": bench_frame(device, args.split_tokens)}))
+        print(json.dumps({"pi05_frame": _frame_both(device, args.split_tokens)}))
         return
     if args.only_arrivals:
         print(json.dumps({"arrival_patterns": bench_arrivals(device, args.split_tokens),
@@ -727,6 +765,8 @@ def main():
     if not args.no_alt_schedules:
         out["step_us_three_launches_per_layer"] = round(s["step_us_separate"], 2)
         out["step_us_merge_append_fused_across_layers"] = round(s["step_us_fused"], 2)
+        out["step_us_recorded_graph"] = round(s["step_us_graph"], 2)
+        out["host_us_per_step_recorded_graph"] = round(s["host_us_per_step_graph"], 1)
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
     if os.path.exists(traffic_file):
         t = json.load(open(traffic_file))
@@ -743,7 +783,7 @@ def main():
         out["cross_task"] = {k: round(v, 2) for k, v in
                              bench_cross_task(device, args.split_tokens).items()}
     if not args.no_frame:
-        out["pi05_frame"] = {k: round(v, 2) for k, v in bench_frame(device, args.split_tokens).items()}
+        out["pi05_frame"] = _frame_both(device, args.split_tokens)
     if not args.no_arrivals:
         out["arrival_patterns"] = bench_arrivals(device, args.split_tokens)
         out["budget_calibration"] = bench_calibration(device, args.split_tokens)

@@ -226,15 +226,29 @@ int32_t oxy_mixed_attention_static(oxy_pool *pool, const oxy_batch *batch, int32
  * k_new / v_new directly and writes them to the pool on the side.  Outputs and pool contents
  * are those of flags = 0.  A batch with an item of more than 2 new tokens on a non-empty own
  * history is not covered; for it the flag is ignored.  Wins over OXY_STEP_FUSE_ACROSS_LAYERS.
+ * OXY_STEP_GRAPH (with any of the above) = the launches of the step are recorded into a HIP graph
+ * the first time a step of this form is seen and replayed with ONE graph launch on hip_stream
+ * from then on: Alg. 1's S denoise steps and k decode steps per frame are short launches, and
+ * issuing 2-3 of them per layer from the host costs more than running them.  "This form" = same
+ * workspace slot, same pointers, strides, scale and layers, same numbers of tokens and work
+ * items; a decode loop with resident buffers meets this on every step until a history crosses a
+ * split boundary.  A step of a new form is recorded again (an existing recording with the same
+ * launch sequence is updated in place once eight are held).  Same kernels, same arguments,
+ * same results bit for bit.  The pool keeps the recordings until it is destroyed; the pointers
+ * must stay valid while steps of that form are replayed.  events must be NULL.
  * events: NULL, or HOST array of 4*(layer_end-layer_begin) created hipEvent_t; per layer they
  * receive the begin and end timestamps of the work-item kernel and of the merge kernel
  * themselves (hipExtLaunchKernel start/stop events; a profiling hook). */
-enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1, OXY_STEP_FOLD_APPEND = 2 };
+enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1, OXY_STEP_FOLD_APPEND = 2, OXY_STEP_GRAPH = 4 };
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,
                         size_t kv_layer_stride, const void *q, void *out, size_t q_layer_stride,
                         float *lse, size_t lse_layer_stride, float scale, int32_t flags,
                         void *const *events, void *hip_stream);
+/* Counters of OXY_STEP_GRAPH since the pool was created (any output may be NULL): recordings
+ * instantiated, recordings updated in place, steps replayed. */
+int32_t oxy_step_graph_stats(oxy_pool *pool, int32_t *instantiations, int32_t *updates,
+                             int32_t *replays);
 /* oxy_stream_append + oxy_mixed_attention of one layer in two launches instead of three: the
  * KV part of Update (App. A.2) folded into the attention work items, see OXY_STEP_FOLD_APPEND.
  * k_new, v_new: DEVICE bf16 [n_tokens][256] of this layer; q, out, lse as oxy_mixed_attention. */

@@ -20,6 +20,7 @@ POOL_HOST_ONLY = 1
 BATCH_APPEND_ONLY = 1
 STEP_FUSE_ACROSS_LAYERS = 1
 STEP_FOLD_APPEND = 2
+STEP_GRAPH = 4
 SCHED_BATCHED, SCHED_UNBATCHED, SCHED_UPPER_BOUND = 0, 1, 2
 
 EXPORTS = [
@@ -28,7 +29,8 @@ EXPORTS = [
     "oxy_prefix_fork",
     "oxy_prefix_release",
     "oxy_stream_create", "oxy_stream_release", "oxy_stream_rewind", "oxy_batch_build",
-    "oxy_stream_append", "oxy_mixed_attention", "oxy_mixed_attention_static", "oxy_step_layers", "oxy_append_attention",
+    "oxy_stream_append", "oxy_mixed_attention", "oxy_mixed_attention_static", "oxy_step_layers", "oxy_step_graph_stats",
+    "oxy_append_attention",
     "oxy_batch_destroy",
     "oxy_gather_kv",
     "oxy_stream_info", "oxy_stream_blocks", "oxy_prefix_info", "oxy_prefix_blocks",
@@ -104,6 +106,7 @@ def lib():
             "oxy_mixed_attention_static": [vp, vp, i32, vp, vp, vp, ctypes.c_float, vp],
             "oxy_step_layers": [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp, ctypes.c_size_t,
                                 vp, ctypes.c_size_t, ctypes.c_float, i32, ctypes.POINTER(vp), vp],
+            "oxy_step_graph_stats": [vp, pi32, pi32, pi32],
             "oxy_append_attention": [vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp],
             "oxy_batch_destroy": [vp],
             "oxy_gather_kv": [vp, i32, ctypes.POINTER(ctypes.c_int64), i32, vp, vp, vp],
@@ -255,6 +258,13 @@ def oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_
     _check(lib().oxy_step_layers(pool, batch, layer_begin, layer_end, k_ptr, v_ptr, kv_layer_stride,
                                  q_ptr, out_ptr, q_layer_stride, lse_ptr or None, lse_layer_stride,
                                  ctypes.c_float(scale), flags, events, stream or None))
+
+
+def oxy_step_graph_stats(pool):
+    """(instantiations, updates, replays) of OXY_STEP_GRAPH on this pool."""
+    a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().oxy_step_graph_stats(pool, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
 
 
 def oxy_append_attention(pool, batch, layer, k_ptr, v_ptr, q_ptr, out_ptr, lse_ptr, scale, stream):

@@ -617,8 +617,13 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
 // ---- stream path: <= 2 query tokens (16 rows, the decode case).  Nothing is shared, so the
 // four wavefronts take the 32-key steps of the split round-robin, stream their pages straight
 // into registers one step ahead, and combine their four results through LDS.
+// kOwnPages: the key range lies in the item's own pages, which no other workgroup of the launch
+// reads (and which receive the item's new rows when the append is folded in); otherwise the
+// pages are a prefix's and other workgroups read them too.
+template <bool kOwnPages>
 __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& wi, char* smem,
-                                            float (*sml)[16][2], char* qs, const bool appends) {
+                                            float (*sml)[16][2], char* qs) {
+  constexpr bool appends = kOwnPages;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int n = lane & 15, g = lane >> 4;
@@ -646,6 +651,13 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   // A wavefront has at most one step in flight beyond the one it computes, and it waits for all
   // of it before the next product, so (unlike the tile path) nothing is lost when the load of
   // a step past the end is simply skipped; a missing page B re-reads page A and is masked.
+  // Own pages are read once per launch, by this workgroup alone: their loads carry the
+  // non-temporal hint, so that they do not push the pages that other workgroups share out of
+  // the L2.
+  auto page_load = [](const char* p) {
+    if constexpr (kOwnPages) return __builtin_nontemporal_load((const u32x4*)p);
+    return *(const u32x4*)p;
+  };
   auto load_k = [&](const int s) {
     if (s >= nsteps) return;
     const int pi = 2 * s;
@@ -653,7 +665,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((n >> 3) ? blk_b : blk_a) * kBlockBytes + lane_k;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) kr[i] = *(const u32x4*)(p + i * 512);
+    for (int i = 0; i < 16; ++i) kr[i] = page_load(p + i * 512);
   };
   auto load_v = [&](const int s) {
     if (s >= nsteps) return;
@@ -662,7 +674,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((g >> 1) ? blk_b : blk_a) * kBlockBytes + lane_v;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) vr[c] = *(const u32x4*)(p + c * 512);
+    for (int c = 0; c < 16; ++c) vr[c] = page_load(p + c * 512);
   };
   // Folded append: the query tokens of a streaming item are its new rows.  Those inside this
   // split's key range are written to the pool by this workgroup (no other workgroup reads
@@ -828,7 +840,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
     else
       tile_path<false>(a, wi, smem, 0);
   } else if (path == PATH_STREAM) {
-    stream_path(a, wi, smem, sml, qs, (path_word & kPathAppends) != 0);
+    if (path_word & kPathAppends)
+      stream_path<true>(a, wi, smem, sml, qs);
+    else
+      stream_path<false>(a, wi, smem, sml, qs);
   } else {
     return;   // padding record
   }

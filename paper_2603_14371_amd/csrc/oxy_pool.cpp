@@ -59,6 +59,37 @@ struct DescSlot {
   char* d_base = nullptr;       // device: descriptor, then partial accumulators, then (m,l)
 };
 
+// Everything a recorded step depends on: two steps with equal keys issue identical launches.
+struct StepKey {
+  const void* d_base = nullptr;
+  const void *k_new = nullptr, *v_new = nullptr, *q = nullptr, *out = nullptr, *lse = nullptr;
+  size_t kv_stride = 0, q_stride = 0, lse_stride = 0;
+  float scale = 0.f;
+  int32_t layer_begin = 0, layer_end = 0, mode = 0;   // mode: 0 separate, 1 fused, 2 folded
+  int32_t n_work = 0, n_tokens = 0, off_work = 0, off_tables = 0, off_part_off = 0,
+          off_n_parts = 0;
+  bool operator==(const StepKey& o) const {
+    return d_base == o.d_base && k_new == o.k_new && v_new == o.v_new && q == o.q &&
+           out == o.out && lse == o.lse && kv_stride == o.kv_stride && q_stride == o.q_stride &&
+           lse_stride == o.lse_stride && scale == o.scale && layer_begin == o.layer_begin &&
+           layer_end == o.layer_end && mode == o.mode && n_work == o.n_work &&
+           n_tokens == o.n_tokens && off_work == o.off_work && off_tables == o.off_tables &&
+           off_part_off == o.off_part_off && off_n_parts == o.off_n_parts;
+  }
+  // same number and kinds of launches in the same order: an instantiated graph can be updated
+  // in place from a recording of the other
+  bool same_topology(const StepKey& o) const {
+    return layer_end - layer_begin == o.layer_end - o.layer_begin && mode == o.mode &&
+           (n_tokens > 0) == (o.n_tokens > 0);
+  }
+};
+struct StepGraph {
+  StepKey key;
+  hipGraphExec_t exec = nullptr;
+  uint64_t last_use = 0;
+};
+constexpr size_t kMaxStepGraphs = 8;
+
 }  // namespace
 
 struct oxy_pool {
@@ -76,6 +107,11 @@ struct oxy_pool {
   std::vector<DescSlot> slots;
   int32_t live_batches = 0;
   uint64_t build_seq = 0;
+  // recorded launch sequences of oxy_step_layers (OXY_STEP_GRAPH)
+  std::vector<StepGraph> graphs;
+  hipStream_t record_stream = nullptr;   // launches are recorded here, never executed here
+  uint64_t graph_clock = 0;
+  int32_t graph_instantiations = 0, graph_updates = 0, graph_replays = 0;
 };
 
 struct oxy_batch {
@@ -83,6 +119,7 @@ struct oxy_batch {
   int32_t slot = -1;
   int32_t flags = 0;
   int32_t n_items = 0, n_tokens = 0, n_work = 0, n_partials = 0;
+  int32_t n_launch = 0;   // n_work rounded up to a multiple of 64 with padding records: the grid
   bool append_foldable = false;   // every item has <= 2 new tokens or an empty own history
   // word offsets inside the descriptor
   int32_t off_slots = 0, off_work = 0, off_toks = 0, off_tables = 0, off_part_off = 0,
@@ -279,6 +316,9 @@ int32_t oxy_pool_destroy(oxy_pool* p) {
       if (s.staging) (void)hipHostFree(s.staging);
     }
   }
+  for (StepGraph& g : p->graphs)
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (p->record_stream) (void)hipStreamDestroy(p->record_stream);
   delete p;
   return OXY_OK;
 }
@@ -751,13 +791,22 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   b->n_partials = (int32_t)n_partials;
   b->off_slots = 0;
   b->append_foldable = foldable;
+  // Sections in the order slots | work | part_off | n_parts | token lists | tables: the block
+  // tables, whose size changes whenever a stream takes a new block, come last, so that the
+  // device addresses of all sections stay the same from step to step while the shape of the
+  // batch (tokens, work items, tile token lists) does -- a recorded launch sequence
+  // (OXY_STEP_GRAPH) can then be replayed unchanged.
+  // The grid is the work list rounded up to a multiple of 64 records (padding records end at
+  // once): the launch shape then changes only every 64 work items, not whenever a history
+  // crosses a split boundary.
+  b->n_launch = std::max(n_work, std::min((n_work + 63) / 64 * 64, c.max_work_items));
   b->off_work = b->off_slots + (int32_t)n_tokens;
-  b->off_toks = b->off_work + n_work * oxy::kWorkWords;
-  b->off_tables = b->off_toks + (int32_t)toks.size();
-  b->off_part_off = b->off_tables + tbl_words;
+  b->off_part_off = b->off_work + b->n_launch * oxy::kWorkWords;
   b->off_n_parts = b->off_part_off + (int32_t)part_off.size();
+  b->off_toks = b->off_n_parts + (int32_t)n_parts.size();
+  b->off_tables = b->off_toks + (int32_t)toks.size();
   std::vector<int32_t>& h = b->host;
-  h.resize((size_t)b->off_n_parts + n_parts.size());
+  h.resize((size_t)b->off_tables + tbl_words);
   if (h.size() > p->desc_words) {   // cannot happen: every section was bounded above
     delete b;
     return fail(OXY_ERR_WORKSPACE, "batch_build: descriptor overflow (internal)");
@@ -784,9 +833,9 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   std::copy(n_parts.begin(), n_parts.end(), h.begin() + b->off_n_parts);
   // Work records, 128 bytes each: header, then inline copies of the tile's token ids and of the
   // block ids of the split's first pages, so a workgroup needs one load before its first pages.
-  for (int32_t i = 0; i < n_work; ++i) {
+  for (int32_t i = 0; i < b->n_launch; ++i) {
     int32_t* w = &h[(size_t)b->off_work + (size_t)i * oxy::kWorkWords];
-    if (order[i] < 0) {
+    if (i >= n_work || order[i] < 0) {
       const int32_t noop[kHdr] = {0, 0, 0, 0, 0, oxy::kNoCausal, 0, oxy::PATH_NOOP};
       std::copy(noop, noop + kHdr, w);
       std::fill(w + kHdr, w + oxy::kWorkWords, 0);
@@ -870,7 +919,7 @@ oxy::AttnArgs attn_args(const oxy_pool* p, const oxy_batch* b, int32_t layer, co
   a.n_parts = d + b->off_n_parts;
   a.part_acc = (uint16_t*)(ds.d_base + p->acc_offset);
   a.part_ml = (float*)(ds.d_base + p->ml_offset);
-  a.n_work = b->n_work;
+  a.n_work = b->n_launch;
   a.n_q = b->n_tokens;
   a.scale = scale;
   a.k_new = a.v_new = nullptr;
@@ -913,57 +962,63 @@ int32_t oxy_mixed_attention_static(oxy_pool* p, const oxy_batch* b, int32_t laye
   return OXY_OK;
 }
 
-int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, int32_t layer_end,
-                        const void* k_new, const void* v_new, size_t kv_layer_stride,
-                        const void* q, void* out, size_t q_layer_stride, float* lse,
-                        size_t lse_layer_stride, float scale, int32_t flags, void* const* events,
-                        void* hip_stream) {
-  if (flags & ~(OXY_STEP_FUSE_ACROSS_LAYERS | OXY_STEP_FOLD_APPEND))
-    return fail(OXY_ERR_INVALID_ARG, "step_layers: flags");
-  if (!p || !b || b->pool != p || !k_new || !v_new || !q || !out || p->host_only)
-    return fail(OXY_ERR_INVALID_ARG, "step_layers: null argument, foreign batch or host-only pool");
-  if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
-    return fail(OXY_ERR_INVALID_ARG, "step_layers: layers [%d, %d)", layer_begin, layer_end);
-  if (b->flags & OXY_BATCH_APPEND_ONLY)
-    return fail(OXY_ERR_INVALID_ARG, "step_layers: batch was built append-only");
-  const bool fold = (flags & OXY_STEP_FOLD_APPEND) != 0 && b->append_foldable;
-  const bool fuse = (flags & OXY_STEP_FUSE_ACROSS_LAYERS) != 0 && !fold;
-  hipStream_t s = (hipStream_t)hip_stream;
+namespace {
+struct StepCall {
+  oxy_pool* p;
+  const oxy_batch* b;
+  int32_t layer_begin, layer_end;
+  const void *k_new, *v_new;
+  size_t kv_layer_stride;
+  const void* q;
+  void* out;
+  size_t q_layer_stride;
+  float* lse;
+  size_t lse_layer_stride;
+  float scale;
+  bool fold, fuse;
+  void* const* events;
+};
+
+// The launches of one step, in order, on stream s.  Same effects as the per-layer calls.  With
+// `fuse`, the merge of layer l and the append of layer l+1 (disjoint memory) share one launch;
+// with `fold`, the work items do the append.
+int32_t issue_step(const StepCall& c, hipStream_t s) {
+  oxy_pool* p = c.p;
+  const oxy_batch* b = c.b;
   const int32_t* d_desc = (const int32_t*)p->slots[b->slot].d_base;
   auto append_of = [&](int32_t layer) {
     oxy::AppendArgs ap;
-    ap.k_new = (const char*)k_new + (size_t)layer * kv_layer_stride;
-    ap.v_new = (const char*)v_new + (size_t)layer * kv_layer_stride;
+    ap.k_new = (const char*)c.k_new + (size_t)layer * c.kv_layer_stride;
+    ap.v_new = (const char*)c.v_new + (size_t)layer * c.kv_layer_stride;
     ap.d_slots = d_desc + b->off_slots;
     ap.n_tokens = b->n_tokens;
     ap.layer_base = layer_base(p, layer);
     return ap;
   };
-  // Same effects as the per-layer calls.  With `fuse`, the merge of layer l and the append of
-  // layer l+1 (disjoint memory) share one launch; with `fold`, the work items do the append.
   auto append_now = [&](int32_t layer) {
     oxy::AppendArgs ap = append_of(layer);
     return oxy::launch_append(ap.k_new, ap.v_new, ap.d_slots, ap.n_tokens, ap.layer_base, s);
   };
-  if (fuse) {
-    hipError_t e = append_now(layer_begin);
+  if (c.fuse) {
+    hipError_t e = append_now(c.layer_begin);
     if (e != hipSuccess) return hip_fail(e, "step_layers: append");
   }
-  for (int32_t layer = layer_begin; layer < layer_end; ++layer) {
-    const size_t i = (size_t)(layer - layer_begin);
+  for (int32_t layer = c.layer_begin; layer < c.layer_end; ++layer) {
+    const size_t i = (size_t)(layer - c.layer_begin);
     hipError_t e = hipSuccess;
-    if (!fuse && !fold) {
+    if (!c.fuse && !c.fold) {
       e = append_now(layer);
       if (e != hipSuccess) return hip_fail(e, "step_layers: append");
     }
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    if (events)
-      for (int j = 0; j < 4; ++j) ev[j] = (hipEvent_t)events[4 * i + j];
-    oxy::AttnArgs a = attn_args(p, b, layer, (const char*)q + (size_t)layer * q_layer_stride,
-                                (char*)out + (size_t)layer * q_layer_stride,
-                                lse ? (float*)((char*)lse + (size_t)layer * lse_layer_stride) : nullptr,
-                                scale);
-    if (fold) {
+    if (c.events)
+      for (int j = 0; j < 4; ++j) ev[j] = (hipEvent_t)c.events[4 * i + j];
+    oxy::AttnArgs a =
+        attn_args(p, b, layer, (const char*)c.q + (size_t)layer * c.q_layer_stride,
+                  (char*)c.out + (size_t)layer * c.q_layer_stride,
+                  c.lse ? (float*)((char*)c.lse + (size_t)layer * c.lse_layer_stride) : nullptr,
+                  c.scale);
+    if (c.fold) {
       const oxy::AppendArgs ap = append_of(layer);
       a.k_new = ap.k_new;
       a.v_new = ap.v_new;
@@ -971,7 +1026,7 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     }
     e = oxy::launch_attention_work(a, s, ev[0], ev[1]);
     if (e != hipSuccess) return hip_fail(e, "step_layers: attention");
-    if (fuse && layer + 1 < layer_end) {
+    if (c.fuse && layer + 1 < c.layer_end) {
       oxy::AppendArgs nx = append_of(layer + 1);
       e = oxy::launch_merge_append(a, &nx, s, ev[2], ev[3]);
     } else {
@@ -979,6 +1034,151 @@ int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, in
     }
     if (e != hipSuccess) return hip_fail(e, "step_layers: merge");
   }
+  return OXY_OK;
+}
+
+// OXY_STEP_GRAPH: the launches of the step are recorded once (stream capture on a stream of the
+// library's own; nothing runs there) and replayed with one graph launch on the caller's stream.
+// A step whose key equals a recorded one replays it as it is; otherwise the step is recorded
+// again and, where a recording with the same sequence of launches exists and the cache is
+// full, that one is updated in place instead of instantiating another.
+int32_t replay_step(const StepCall& c, hipStream_t s) {
+  oxy_pool* p = c.p;
+  const oxy_batch* b = c.b;
+  StepKey key;
+  key.d_base = p->slots[b->slot].d_base;
+  key.k_new = c.k_new;
+  key.v_new = c.v_new;
+  key.q = c.q;
+  key.out = c.out;
+  key.lse = c.lse;
+  key.kv_stride = c.kv_layer_stride;
+  key.q_stride = c.q_layer_stride;
+  key.lse_stride = c.lse_layer_stride;
+  key.scale = c.scale;
+  key.layer_begin = c.layer_begin;
+  key.layer_end = c.layer_end;
+  key.mode = c.fold ? 2 : c.fuse ? 1 : 0;
+  key.n_work = b->n_launch;
+  key.n_tokens = b->n_tokens;
+  key.off_work = b->off_work;
+  key.off_tables = b->off_tables;
+  key.off_part_off = b->off_part_off;
+  key.off_n_parts = b->off_n_parts;
+  const uint64_t now = ++p->graph_clock;
+  StepGraph* hit = nullptr;
+  for (StepGraph& g : p->graphs)
+    if (g.key == key) {
+      hit = &g;
+      break;
+    }
+  if (!hit) {
+    hipError_t e = hipSuccess;
+    if (!p->record_stream) {
+      e = hipStreamCreateWithFlags(&p->record_stream, hipStreamNonBlocking);
+      if (e != hipSuccess) return hip_fail(e, "step_layers: stream for recording");
+    }
+    e = hipStreamBeginCapture(p->record_stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return hip_fail(e, "step_layers: begin recording");
+    const int32_t rc = issue_step(c, p->record_stream);
+    hipGraph_t graph = nullptr;
+    e = hipStreamEndCapture(p->record_stream, &graph);   // always: leaves recording mode
+    if (rc != OXY_OK) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return rc;
+    }
+    if (e != hipSuccess || !graph) return hip_fail(e, "step_layers: end recording");
+    // a victim to update in place: least recently used recording with the same launch sequence,
+    // taken only when the cache is full
+    StepGraph* victim = nullptr;
+    if (p->graphs.size() >= kMaxStepGraphs) {
+      for (StepGraph& g : p->graphs)
+        if (g.key.same_topology(key) && (!victim || g.last_use < victim->last_use)) victim = &g;
+      if (!victim) {   // none fits: drop the least recently used one
+        size_t lru = 0;
+        for (size_t i = 1; i < p->graphs.size(); ++i)
+          if (p->graphs[i].last_use < p->graphs[lru].last_use) lru = i;
+        (void)hipGraphExecDestroy(p->graphs[lru].exec);
+        p->graphs.erase(p->graphs.begin() + lru);
+      }
+    }
+    if (victim) {
+      hipGraphNode_t bad = nullptr;
+      hipGraphExecUpdateResult res = hipGraphExecUpdateSuccess;
+      e = hipGraphExecUpdate(victim->exec, graph, &bad, &res);
+      if (e == hipSuccess && res == hipGraphExecUpdateSuccess) {
+        victim->key = key;
+        hit = victim;
+        p->graph_updates++;
+      } else {
+        (void)hipGetLastError();
+        (void)hipGraphExecDestroy(victim->exec);
+        p->graphs.erase(p->graphs.begin() + (victim - p->graphs.data()));
+      }
+    }
+    if (!hit) {
+      hipGraphExec_t exec = nullptr;
+      e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return hip_fail(e, "step_layers: instantiate the recorded step");
+      }
+      p->graphs.push_back(StepGraph{key, exec, now});
+      hit = &p->graphs.back();
+      p->graph_instantiations++;
+    }
+    (void)hipGraphDestroy(graph);
+  }
+  hit->last_use = now;
+  hipError_t e = hipGraphLaunch(hit->exec, s);
+  if (e != hipSuccess) return hip_fail(e, "step_layers: replay");
+  p->graph_replays++;
+  return OXY_OK;
+}
+}  // namespace
+
+int32_t oxy_step_layers(oxy_pool* p, const oxy_batch* b, int32_t layer_begin, int32_t layer_end,
+                        const void* k_new, const void* v_new, size_t kv_layer_stride,
+                        const void* q, void* out, size_t q_layer_stride, float* lse,
+                        size_t lse_layer_stride, float scale, int32_t flags, void* const* events,
+                        void* hip_stream) {
+  if (flags & ~(OXY_STEP_FUSE_ACROSS_LAYERS | OXY_STEP_FOLD_APPEND | OXY_STEP_GRAPH))
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: flags");
+  if (!p || !b || b->pool != p || !k_new || !v_new || !q || !out || p->host_only)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: null argument, foreign batch or host-only pool");
+  if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: layers [%d, %d)", layer_begin, layer_end);
+  if (b->flags & OXY_BATCH_APPEND_ONLY)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: batch was built append-only");
+  if ((flags & OXY_STEP_GRAPH) && events)
+    return fail(OXY_ERR_INVALID_ARG, "step_layers: timing events cannot go into a recorded step");
+  StepCall c;
+  c.p = p;
+  c.b = b;
+  c.layer_begin = layer_begin;
+  c.layer_end = layer_end;
+  c.k_new = k_new;
+  c.v_new = v_new;
+  c.kv_layer_stride = kv_layer_stride;
+  c.q = q;
+  c.out = out;
+  c.q_layer_stride = q_layer_stride;
+  c.lse = lse;
+  c.lse_layer_stride = lse_layer_stride;
+  c.scale = scale;
+  c.fold = (flags & OXY_STEP_FOLD_APPEND) != 0 && b->append_foldable;
+  c.fuse = (flags & OXY_STEP_FUSE_ACROSS_LAYERS) != 0 && !c.fold;
+  c.events = events;
+  if (flags & OXY_STEP_GRAPH) return replay_step(c, (hipStream_t)hip_stream);
+  return issue_step(c, (hipStream_t)hip_stream);
+}
+
+int32_t oxy_step_graph_stats(oxy_pool* p, int32_t* instantiations, int32_t* updates,
+                             int32_t* replays) {
+  if (!p) return fail(OXY_ERR_INVALID_ARG, "step_graph_stats: null");
+  if (instantiations) *instantiations = p->graph_instantiations;
+  if (updates) *updates = p->graph_updates;
+  if (replays) *replays = p->graph_replays;
   return OXY_OK;
 }
 

@@ -52,6 +52,46 @@ hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, h
   if (e == hipSuccess) memcpy(dst, src, n);   // the sanitizer checks both ranges
   return e;
 }
+// recorded launch sequences: a stream, a graph and an instantiated graph are small heap objects,
+// so that the sanitizer sees every leak, double free and use after free of the host logic
+hipError_t hipGetLastError(void) { return hipSuccess; }
+hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned) {
+  *s = (hipStream_t)malloc(8);
+  return hipSuccess;
+}
+hipError_t hipStreamDestroy(hipStream_t s) {
+  free((void*)s);
+  return hipSuccess;
+}
+hipError_t hipStreamBeginCapture(hipStream_t, hipStreamCaptureMode) { return outcome(); }
+hipError_t hipStreamEndCapture(hipStream_t, hipGraph_t* g) {
+  *g = (hipGraph_t)malloc(8);
+  return hipSuccess;
+}
+hipError_t hipGraphDestroy(hipGraph_t g) {
+  free((void*)g);
+  return hipSuccess;
+}
+hipError_t hipGraphInstantiate(hipGraphExec_t* x, hipGraph_t, hipGraphNode_t*, char*, size_t) {
+  hipError_t e = outcome();
+  if (e == hipSuccess) *x = (hipGraphExec_t)malloc(8);
+  return e;
+}
+hipError_t hipGraphExecDestroy(hipGraphExec_t x) {
+  free((void*)x);
+  return hipSuccess;
+}
+hipError_t hipGraphExecUpdate(hipGraphExec_t x, hipGraph_t, hipGraphNode_t*,
+                              hipGraphExecUpdateResult* res) {
+  *(volatile char*)x;   // must still be alive
+  hipError_t e = outcome();
+  *res = e == hipSuccess ? hipGraphExecUpdateSuccess : hipGraphExecUpdateError;
+  return e;
+}
+hipError_t hipGraphLaunch(hipGraphExec_t x, hipStream_t) {
+  *(volatile char*)x;
+  return outcome();
+}
 hipError_t hipMemsetAsync(void* dst, int v, size_t n, hipStream_t) {
   hipError_t e = outcome();
   if (e == hipSuccess) memset(dst, v, n);

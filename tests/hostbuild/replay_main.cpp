@@ -154,7 +154,7 @@ int main(int argc, char** argv) {
           if (!(flags & OXY_BATCH_APPEND_ONLY)) {
             CHECK(oxy_mixed_attention(pool, b, n_layers - 1, p, p, nullptr, 0.0625f, nullptr) == OXY_OK,
                   "mixed_attention");
-            for (int f = 0; f < 4; ++f)
+            for (int f = 0; f < 8; ++f)   // every launch schedule, issued and recorded
               CHECK(oxy_step_layers(pool, b, 0, n_layers, p, p, 0, p, p, 0, nullptr, 0, 0.0625f, f,
                                     nullptr, nullptr) == OXY_OK, "step_layers flags %d", f);
           }
