@@ -145,7 +145,7 @@ def _live_kv_tokens(gw, items):
 def bench_stress(args, device, workload=None, alt_schedules=True):
     import torch
     from paper_2603_14371_amd import synth
-    w = workload or synth.stress(mixed_steps=2 * args.warmup + 5 * args.steps + 2)
+    w = workload or synth.stress(mixed_steps=2 * args.warmup + 9 * args.steps + 2)
     t0 = time.time()
     n_streams = max(len(op["items"]) for op in w["trace"] if op["op"] == "step")
     gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens,
@@ -169,6 +169,16 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
         host_us.append((time.perf_counter() - h0) * 1e6)
     torch.cuda.synchronize(device)
     step_us = (time.perf_counter() - t_start) / args.steps * 1e6
+    # ---- spread: four more blocks of `steps` steps each, timed the same way
+    block_us = [step_us]
+    for blk in range(4 if alt_schedules else 0):
+        first = 2 * args.warmup + (5 + blk) * args.steps
+        torch.cuda.synchronize(device)
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            runner.step(steps[first + i]["items"])
+        torch.cuda.synchronize(device)
+        block_us.append((time.perf_counter() - t_start) / args.steps * 1e6)
     # ---- the same steps again with HIP events around every attention launch (on the stream the
     # kernels run on) for the roofline figure
     sets = [EventSet(gw.n_layers) for _ in range(args.steps)]
@@ -219,6 +229,7 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
     achieved = alg_bytes / (attn_avg_us * 1e-6) / 1e9
     res = {
         "step_us": step_us,
+        "step_us_blocks": [round(b, 2) for b in block_us],
         "step_us_with_events": step_us_ev,
         "step_us_separate": other["separate"],
         "step_us_fused": other["fuse"],
@@ -396,6 +407,61 @@ def bench_cross_task(device, split_tokens, n_steps=64, reps=3):
     out["speedup_vs_isolated"] = out["isolated_us"] / out["shared_us"]
     out["steps"] = n_steps
     return out
+
+
+def bench_cross_frame(device, split_tokens, frames=40, warm=16):
+    """Config 2 as stated: 8 request slots carried across frames, targets ~U{16..512}, k = 10
+    tokens per frame, a fresh 832-token prefix and one 50-query x 10-step chunk per frame, page
+    16 on a shuffled free order, 18 layers.  Per frame: prefix KV write, fan-out, 10 mixed steps
+    (host-synchronised per step, as a decode loop is), releases.  Frames after `warm` are timed:
+    by then all eight slots are occupied and histories span 1..~400 own tokens."""
+    import torch
+    from paper_2603_14371_amd import binding as B, synth
+    from paper_2603_14371_amd.harness import GpuWorld
+    w = synth.cross_frame(n_frames=frames)
+    gw = GpuWorld(w, None, device=device, split_tokens=split_tokens, want_lse=False)
+    L = gw.n_layers
+    gen = torch.Generator(device=device)
+    gen.manual_seed(11)
+    pk = torch.randn((L, 2, 832, 256), device=device, generator=gen).to(torch.bfloat16)
+    runners = {}
+    stream = torch.cuda.current_stream(device).cuda_stream
+    frame_us, step_us, batch = [], [], []
+    own = {}
+    for f, (lo, hi) in enumerate(w["frames"]):
+        torch.cuda.synchronize(device)
+        t_frame = time.perf_counter()
+        for op in w["trace"][lo:hi]:
+            if op["op"] == "prefix_append":
+                B.oxy_prefix_append_layers(gw.pool, op["pid"], 0, L, pk[0, 0].data_ptr(),
+                                           pk[0, 1].data_ptr(), pk.stride(0) * 2, op["n"],
+                                           op["pos0"], stream)
+            elif op["op"] == "step":
+                n_tok = sum(n for _, n in op["items"])
+                if n_tok not in runners:
+                    runners[n_tok] = StepRunner(gw, n_tok, device, 100 + n_tok)
+                t0 = time.perf_counter()
+                runners[n_tok].step(op["items"])
+                torch.cuda.synchronize(device)
+                if f >= warm:
+                    step_us.append((time.perf_counter() - t0) * 1e6)
+                    batch.append(len(op["items"]) - 1)
+                for sid, n in op["items"]:
+                    if n == 1:
+                        own[sid] = own.get(sid, 0) + 1
+            else:
+                gw.apply(op)
+        torch.cuda.synchronize(device)
+        if f >= warm:
+            frame_us.append((time.perf_counter() - t_frame) * 1e6)
+    gw.close()
+    fr = float(np.median(frame_us))
+    return {"frames_timed": len(frame_us), "frame_us_median": fr,
+            "frame_us_min": float(np.min(frame_us)), "frame_us_max": float(np.max(frame_us)),
+            "mixed_step_us_median": float(np.median(step_us)),
+            "decode_batch_mean": float(np.mean(batch)),
+            "longest_own_history": int(max(own.values())),
+            "action_hz": 1e6 / fr, "decode_tokens_per_s": float(np.mean(batch)) * 10 / (fr * 1e-6)}
 
 
 def _arrival_patterns(frames, seed=14371300):
@@ -730,7 +796,8 @@ def main():
         print(json.dumps({k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()}))
         return
     if args.only_frame:
-        print(json.dumps({"pi05_frame": _frame_both(device, args.split_tokens)}))
+        print(json.dumps({"pi05_frame": _frame_both(device, args.split_tokens),
+                          "cross_frame": bench_cross_frame(device, args.split_tokens)}))
         return
     if args.only_arrivals:
         print(json.dumps({"arrival_patterns": bench_arrivals(device, args.split_tokens),
@@ -759,6 +826,12 @@ def main():
                      "merge_launch_us": round(s["merge_launch_us"], 2),
                      "alg_bytes_per_launch": round(s["alg_bytes_per_launch"])},
     }
+    blk = s["step_us_blocks"]
+    out["value_spread"] = {"blocks_of_steps": len(blk), "us_per_step": blk, "min": min(blk),
+                           "median": round(float(np.median(blk)), 2), "max": max(blk),
+                           "note": "value is the first block; the others repeat it on later steps"}
+    with_merge = s["alg_bytes_per_launch"] / ((s["attn_launch_us"] + s["merge_launch_us"]) * 1e-6) / 1e9
+    out["roofline"]["frac_attention_plus_merge"] = round(with_merge / HBM_PEAK_GBPS, 4)
     out["launch_schedule"] = "per layer: work items (new rows appended by the work items " \
                              "themselves) + merge"
     out["step_us_with_events"] = round(s["step_us_with_events"], 2)
@@ -784,6 +857,8 @@ def main():
                              bench_cross_task(device, args.split_tokens).items()}
     if not args.no_frame:
         out["pi05_frame"] = _frame_both(device, args.split_tokens)
+        out["cross_frame"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in
+                              bench_cross_frame(device, args.split_tokens).items()}
     if not args.no_arrivals:
         out["arrival_patterns"] = bench_arrivals(device, args.split_tokens)
         out["budget_calibration"] = bench_calibration(device, args.split_tokens)
