@@ -250,34 +250,42 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
     return res
 
 
-def bench_sweep(args, device, counts=(64, 128, 256, 512)):
+def bench_sweep(args, device, counts=(64, 128, 256, 512), splits=((0, 0), (512, 512))):
     """The stress geometry at growing stream counts (groups of 8 streams per 2048-token prefix,
     own histories ~U{1..2048}, two action chunks): where the work-item kernel gets to on the
     HBM roofline as a launch grows.  The number of layers shrinks as the streams grow so that
     every point cycles through at least ~1.5 GB of distinct KV (the memory-side cache holds
-    256 MB) without filling the card."""
+    256 MB) without filling the card.  Two series: the default split sizes of the pool (256
+    tokens per work item on these lengths, what the 64-stream launch needs to fill the chip)
+    and 512-token work items (pool configuration split_tokens = stream_split_tokens = 512), which
+    pay off once a launch has several times more work items than the chip holds at once."""
     import argparse as _ap
     import torch
     from paper_2603_14371_amd import synth
     out = []
-    for n in counts:
-        layers = max(3, -(-18 * 64 // n))
-        blocks = 8192 * n // 64
-        a = _ap.Namespace(**vars(args))
-        a.steps, a.warmup = max(4, args.steps // 2), 2
-        w = synth.stress(n_layers=layers, n_streams=n, num_blocks=blocks,
-                         mixed_steps=a.warmup + 2 * a.steps + 2)
-        r = bench_stress(a, device, workload=w, alt_schedules=False)
-        out.append({"streams": n, "layers": layers,
-                    "alg_bytes_per_launch": round(r["alg_bytes_per_launch"]),
-                    "attn_launch_us": round(r["attn_launch_us"], 2),
-                    "merge_launch_us": round(r["merge_launch_us"], 2),
-                    "gbps": round(r["kv_gbps"], 1),
-                    "frac": round(r["kv_gbps"] / HBM_PEAK_GBPS, 4),
-                    "frac_with_merge": round(r["alg_bytes_per_launch"] / (
-                        (r["attn_launch_us"] + r["merge_launch_us"]) * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                    "step_us": round(r["step_us"], 1)})
-        torch.cuda.empty_cache()
+    for split, stream_split in splits:
+        for n in counts:
+            layers = max(3, -(-18 * 64 // n))
+            blocks = 8192 * n // 64
+            a = _ap.Namespace(**vars(args))
+            a.steps, a.warmup = max(4, args.steps // 2), 2
+            a.split_tokens = split or args.split_tokens
+            a.stream_split_tokens = stream_split or args.stream_split_tokens
+            w = synth.stress(n_layers=layers, n_streams=n, num_blocks=blocks,
+                             mixed_steps=a.warmup + 2 * a.steps + 2)
+            r = bench_stress(a, device, workload=w, alt_schedules=False)
+            both = r["attn_launch_us"] + r["merge_launch_us"]
+            out.append({"streams": n, "layers": layers,
+                        "tokens_per_work_item": a.split_tokens or 256,
+                        "alg_bytes_per_launch": round(r["alg_bytes_per_launch"]),
+                        "attn_launch_us": round(r["attn_launch_us"], 2),
+                        "merge_launch_us": round(r["merge_launch_us"], 2),
+                        "gbps": round(r["kv_gbps"], 1),
+                        "frac": round(r["kv_gbps"] / HBM_PEAK_GBPS, 4),
+                        "frac_with_merge": round(r["alg_bytes_per_launch"] / (both * 1e-6) / 1e9
+                                                 / HBM_PEAK_GBPS, 4),
+                        "step_us": round(r["step_us"], 1)})
+            torch.cuda.empty_cache()
     return out
 
 
