@@ -472,6 +472,54 @@ def bench_cross_frame(device, split_tokens, frames=40, warm=16):
             "action_hz": 1e6 / fr, "decode_tokens_per_s": float(np.mean(batch)) * 10 / (fr * 1e-6)}
 
 
+def bench_action(args, device, n_chunks=8, chunk=50):
+    """The action-chunk path alone: n_chunks chunks of 50 queries, each on a prefix of its own,
+    no decode items -- the dense (MFMA) side of the method in isolation.  Two geometries: the
+    pi0.5 prefix (832 tokens: prefix phase as streamed token pairs, chunk phase as tiles that
+    read the step's new rows) and the stress prefix (2048 tokens: prefix phase as 8-token
+    tiles).  Reports the work-item kernel's time per layer and its matrix-core rate: executed
+    (counters, see profiles/) = what the kernel issues: row blocks padded to 16, P as hi+lo;
+    algorithmic = 4*8*256 flop per (query token, visible key)."""
+    import torch
+    from paper_2603_14371_amd import synth
+    out = {}
+    for prefix_len in (832, 2048):
+        b = synth._TraceBuilder()
+        pids = [b.prefix(prefix_len) for _ in range(n_chunks)]
+        acts = [b.stream(pid, synth.ACTION) for pid in pids]
+        for _ in range(args.warmup + 2 * args.steps):
+            b.step([(a, chunk) for a in acts], mixed=True)
+        w = synth._workload("action_only", 14371700, 18, 2048, b.trace)
+        gw, rest = _build_state(w, device, args.split_tokens, args.stream_split_tokens)
+        steps = [op for op in rest if op["op"] == "step"]
+        n_tok = n_chunks * chunk
+        runner = StepRunner(gw, n_tok, device, 17)
+        for i in range(args.warmup):
+            runner.step(steps[i]["items"])
+        torch.cuda.synchronize(device)
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            runner.step(steps[args.warmup + i]["items"])
+        torch.cuda.synchronize(device)
+        step_us = (time.perf_counter() - t0) / args.steps * 1e6
+        sets = [EventSet(gw.n_layers) for _ in range(args.steps)]
+        for i in range(args.steps):
+            runner.step(steps[args.warmup + args.steps + i]["items"], sets[i].raw)
+        torch.cuda.synchronize(device)
+        attn_us = float(np.mean([t for es in sets for t in es.work_us()]))
+        merge_us = float(np.mean([t for es in sets for t in es.merge_us()]))
+        flop = 4.0 * 8 * 256 * n_tok * (prefix_len + chunk)
+        out["prefix_%d" % prefix_len] = {
+            "q_tokens": n_tok, "step_us": round(step_us, 2), "attn_launch_us": round(attn_us, 2),
+            "merge_launch_us": round(merge_us, 2),
+            "algorithmic_gflop_per_launch": round(flop / 1e9, 3),
+            "algorithmic_tflops": round(flop / (attn_us * 1e-6) / 1e12, 1),
+            "frac_of_bf16_mfma_peak_algorithmic": round(flop / (attn_us * 1e-6) / 1e12 / 2500.0, 4),
+        }
+        gw.close()
+    return out
+
+
 def _arrival_patterns(frames, seed=14371300):
     """Arrival patterns of the paper's workload generalisation (Sec. 4.4): per frame the list
     of total decode lengths N of the observations that arrive (seeded, synthetic)."""
@@ -782,6 +830,8 @@ def main():
                     help="run only the stream-count sweep (64..512 streams, stress geometry)")
     ap.add_argument("--only-stress", action="store_true",
                     help="profiling aid: the stress section only")
+    ap.add_argument("--only-action", action="store_true",
+                    help="only the action-chunk path in isolation (MFMA rate of the dense side)")
     ap.add_argument("--only-frame", action="store_true",
                     help="profiling aid: run only the pi0.5-shaped frame section")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -802,6 +852,9 @@ def main():
     if args.only_stress:
         s = bench_stress(args, device)
         print(json.dumps({k: (round(v, 2) if isinstance(v, float) else v) for k, v in s.items()}))
+        return
+    if args.only_action:
+        print(json.dumps({"action_only": bench_action(args, device)}))
         return
     if args.only_frame:
         print(json.dumps({"pi05_frame": _frame_both(device, args.split_tokens),
@@ -850,10 +903,17 @@ def main():
         out["host_us_per_step_recorded_graph"] = round(s["host_us_per_step_graph"], 1)
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic_stress.json")
     if os.path.exists(traffic_file):
+        import hashlib
         t = json.load(open(traffic_file))
+        src = os.path.join(ROOT, "paper_2603_14371_amd", "csrc", "oxy_kernels.hip")
+        now = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
         out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
         out["roofline"]["traffic_source"] = "profiles/pmc_traffic_stress.json (rocprofv3 --pmc " \
                                             "FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size)"
+        # the counters cannot be read from inside this process: the figure is the committed one,
+        # stamped with the kernel source it was measured on
+        out["roofline"]["traffic_measured_at_commit"] = t.get("measured_at_commit")
+        out["roofline"]["traffic_kernel_source_unchanged"] = t.get("kernel_source_sha256_16") == now
     sp = stream_probe(device, s["alg_bytes_per_launch"])
     out["roofline"]["plain_streaming_kernel"] = sp
     out["roofline"]["frac_of_plain_streaming_same_bytes"] = round(
@@ -864,6 +924,7 @@ def main():
         out["cross_task"] = {k: round(v, 2) for k, v in
                              bench_cross_task(device, args.split_tokens).items()}
     if not args.no_frame:
+        out["action_only"] = bench_action(args, device)
         out["pi05_frame"] = _frame_both(device, args.split_tokens)
         out["cross_frame"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in
                               bench_cross_frame(device, args.split_tokens).items()}
