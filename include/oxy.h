@@ -236,9 +236,10 @@ int32_t oxy_mixed_attention_static(oxy_pool *pool, const oxy_batch *batch, int32
  * launch sequence is updated in place once eight are held).  Same kernels, same arguments,
  * same results bit for bit.  The pool keeps the recordings until it is destroyed; the pointers
  * must stay valid while steps of that form are replayed.  events must be NULL.
- * events: NULL, or HOST array of 4*(layer_end-layer_begin) created hipEvent_t; per layer they
- * receive the begin and end timestamps of the work-item kernel and of the merge kernel
- * themselves (hipExtLaunchKernel start/stop events; a profiling hook). */
+ * events: NULL, or HOST array of 4*(layer_end-layer_begin) entries, each a created hipEvent_t or
+ * NULL; per layer they receive the begin and end timestamps of the work-item kernel and of the
+ * merge kernel themselves (hipExtLaunchKernel start/stop events; a profiling hook).  A launch
+ * whose two entries are NULL is issued exactly as without events. */
 enum { OXY_STEP_FUSE_ACROSS_LAYERS = 1, OXY_STEP_FOLD_APPEND = 2, OXY_STEP_GRAPH = 4 };
 int32_t oxy_step_layers(oxy_pool *pool, const oxy_batch *batch, int32_t layer_begin,
                         int32_t layer_end, const void *k_new, const void *v_new,
