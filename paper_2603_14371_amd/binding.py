@@ -81,6 +81,14 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise OSError("liboxy.so is not built: run `python -m paper_2603_14371_amd.build` "
                           "(or __graft_entry__.build()) first")
+        # torch ships a HIP runtime of its own under the same library name as the system's: the
+        # one that is loaded first serves the whole process, and device buffers come from torch,
+        # so torch's has to be the one (the system's, loaded first, does not find the device
+        # once torch's other libraries are in)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         L.oxy_last_error.restype = ctypes.c_char_p
         L.oxy_kv_bytes.restype = ctypes.c_size_t
