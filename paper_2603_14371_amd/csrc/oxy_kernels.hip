@@ -318,11 +318,24 @@ struct WorkItem {
   int rec;   // this lane's word of the 32-word record (lanes 32..63 mirror 0..31)
 };
 
-// block ids of the split, one per lane: from the record's inline copy when the split has at
-// most 16 pages (no dependent load), else from the block table
-__device__ __forceinline__ int split_block_ids(const WorkItem& wi, const int lane, const int npg) {
-  if (npg <= kWorkInlinePages) return __shfl(wi.rec, 16 + (lane & 15));
-  return wi.tbl[(wi.kv_begin >> 4) + (lane < npg ? lane : 0)];
+// Block ids of the split, one per lane: the first 16 pages from the record's inline copy (no
+// dependent load), all pages (a split has at most 64) from the block table.  The table load is
+// issued whether or not the split has more than 16 pages: a load under a condition would make
+// the compiler wait for EVERYTHING in flight wherever the two paths meet again (it counts
+// outstanding loads per control-flow path), and that wait would sit in front of the first pages.
+struct SplitIds {
+  int lo, hi;
+};
+__device__ __forceinline__ SplitIds split_block_ids(const WorkItem& wi, const int lane, const int npg) {
+  SplitIds ids;
+  ids.lo = __shfl(wi.rec, 16 + (lane & 15));
+  ids.hi = wi.tbl[(wi.kv_begin >> 4) + (lane < npg ? lane : npg - 1)];
+  return ids;
+}
+// pi is wave-uniform
+__device__ __forceinline__ int block_of(const SplitIds& ids, const int pi) {
+  return pi < kWorkInlinePages ? __builtin_amdgcn_readlane(ids.lo, pi)
+                               : __builtin_amdgcn_readlane(ids.hi, pi);
 }
 
 // ---- tile path: <= 8 query tokens (64 rows); the four wavefronts share every KV page through
@@ -358,7 +371,7 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   // block ids of the whole split, one per lane (a split has at most 64 pages): fetched once,
   // then read with v_readlane, so no step waits on a scalar load before issuing its pages
   const int npg = ((wi.kv_end + 15) >> 4) - (wi.kv_begin >> 4);
-  const int ids = split_block_ids(wi, lane, npg);
+  const SplitIds ids = split_block_ids(wi, lane, npg);
   // Every fetch issues exactly eight loads and no fetch is conditional: the compiler counts
   // outstanding loads per control-flow path, and a conditional load would make it wait for
   // everything at the next join.  A step past the end re-reads one hot 4 KiB (eight times the
@@ -420,8 +433,8 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     }
     const int pi = real ? 2 * s : 0;                      // page index inside the split
     const int o = real ? 1 : 0;
-    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
-    const int blk_b = __builtin_amdgcn_readlane(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
+    const int blk_a = block_of(ids, pi);
+    const int blk_b = block_of(ids, (real && pi + 1 < npg) ? pi + 1 : pi);
     const char* pa = base + (size_t)blk_a * kBlockBytes + tid * 16;
     const char* pb = base + (size_t)blk_b * kBlockBytes + tid * 16;
     st[0] = *(const u32x4*)(pa);
@@ -523,26 +536,31 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   // tokens'.  All eight rows are loaded first (the record repeats the last token id for a
   // short tile), the stores follow once the first pages have been waited for anyway.
   RowPart rows[kFresh ? 8 : 1];
-  int32_t row_slot[kFresh ? 8 : 1];
+  int32_t slot8 = 0;   // lane j % 8: pool slot of the record's token j
   const bool writes_rows = kFresh && wi.kv_begin == 0;
   if constexpr (kFresh) {
-    if (writes_rows) {
+    // loaded by every fresh tile, stored only by the tile of split 0: loads under a condition
+    // would be waited for where the paths meet, in front of the queries and the first keys
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
-        rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
-                           (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
-        row_slot[t] = a.d_slots[tk];
-      }
+    for (int t = 0; t < 8; ++t) {
+      const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
+      rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
+                         (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
     }
+    // one load per lane instead of one wave-uniform load per token: a uniform value is wanted
+    // in a scalar register, i.e. waited for right where it is loaded
+    slot8 = a.d_slots[__shfl(wi.rec, 8 + (lane & 7))];
   }
   {  // the query rows are requested first: loads complete in order per wavefront, and the
      // first product should wait for step 0 only, not for step 1 as well
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+      // unconditional (a row past the tile's tokens re-reads its last token's row, see `tok`)
+      // and zeroed afterwards: see split_block_ids for why no load sits under a condition
       const u32x4 z = {0, 0, 0, 0};
-      qf[j] = row_valid ? *(const u32x4*)(qrow + j * 64 + g * 16) : z;
+      const u32x4 x = *(const u32x4*)(qrow + j * 64 + g * 16);
+      qf[j] = row_valid ? x : z;
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -569,7 +587,8 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     if (writes_rows) {
 #pragma unroll
       for (int t = 0; t < 8; ++t)
-        if (t < wi.n_tok) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
+        if (t < wi.n_tok)
+          store_row(rows[t], __builtin_amdgcn_readlane(slot8, t), (char*)a.layer_base, tid);
     }
   }
   __syncthreads();
@@ -645,7 +664,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
 
   u32x4 kr[16], vr[16];   // kr[2j+hf]: K chunk of (j, hf); vr[c]: V chunk of block c
   const int npg = ((wi.kv_end + 15) >> 4) - (wi.kv_begin >> 4);
-  const int ids = split_block_ids(wi, lane, npg);
+  const SplitIds ids = split_block_ids(wi, lane, npg);
   const int lane_k = (g * 8 + (n & 7)) * 16;
   const int lane_v = kPageBytes + ((g & 1) * 16 + n) * 16;
   // A wavefront has at most one step in flight beyond the one it computes, and it waits for all
@@ -658,23 +677,27 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     if constexpr (kOwnPages) return __builtin_nontemporal_load((const u32x4*)p);
     return *(const u32x4*)p;
   };
-  auto load_k = [&](const int s) {
-    if (s >= nsteps) return;
+  auto load_k_at = [&](const int s) {
     const int pi = 2 * s;
-    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
-    const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
+    const int blk_a = block_of(ids, pi);
+    const int blk_b = block_of(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((n >> 3) ? blk_b : blk_a) * kBlockBytes + lane_k;
 #pragma unroll
     for (int i = 0; i < 16; ++i) kr[i] = page_load(p + i * 512);
   };
-  auto load_v = [&](const int s) {
-    if (s >= nsteps) return;
+  auto load_v_at = [&](const int s) {
     const int pi = 2 * s;
-    const int blk_a = __builtin_amdgcn_readlane(ids, pi);
-    const int blk_b = __builtin_amdgcn_readlane(ids, pi + 1 < npg ? pi + 1 : pi);
+    const int blk_a = block_of(ids, pi);
+    const int blk_b = block_of(ids, pi + 1 < npg ? pi + 1 : pi);
     const char* p = base + (size_t)((g >> 1) ? blk_b : blk_a) * kBlockBytes + lane_v;
 #pragma unroll
     for (int c = 0; c < 16; ++c) vr[c] = page_load(p + c * 512);
+  };
+  auto load_k = [&](const int s) {
+    if (s < nsteps) load_k_at(s);
+  };
+  auto load_v = [&](const int s) {
+    if (s < nsteps) load_v_at(s);
   };
   // Folded append: the query tokens of a streaming item are its new rows.  Those inside this
   // split's key range are written to the pool by this workgroup (no other workgroup reads
@@ -683,7 +706,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   // barrier below anyway, the stores wait there; otherwise they go out, with a barrier of their
   // own, before the first page load.
   RowPart rows[2];
-  int32_t row_slot[2] = {0, 0};
+  int32_t slot2 = 0;   // lane j % 2: pool slot of the record's token j
   bool row_mine[2] = {false, false};
   bool early = false;
   const bool fold = a.k_new && appends;
@@ -696,14 +719,15 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
       rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
                          (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
-      row_slot[t] = a.d_slots[tk];
     }
+    slot2 = a.d_slots[__shfl(wi.rec, 8 + (lane & 1))];   // per lane: see the fresh tiles
     const int first_new = (max(pos0, wi.kv_begin) - wi.kv_begin) >> 5;
     early = first_new < 4;
     if (early) {
 #pragma unroll
       for (int t = 0; t < 2; ++t)
-        if (row_mine[t]) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
+        if (row_mine[t])
+          store_row(rows[t], __builtin_amdgcn_readlane(slot2, t), (char*)a.layer_base, tid);
       __syncthreads();
     }
   }
@@ -716,19 +740,26 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-      qtmp[jj] = row_valid ? *(const u32x4*)(qrow + (2 * wv + jj) * 64 + g * 16) : z;
+    for (int jj = 0; jj < 2; ++jj) {   // unconditional, zeroed afterwards (see split_block_ids)
+      const u32x4 x = *(const u32x4*)(qrow + (2 * wv + jj) * 64 + g * 16);
+      qtmp[jj] = row_valid ? x : z;
+    }
   }
   int s = wv;
-  load_k(s);
-  load_v(s);
+  // The first step's loads are unconditional as well: a wavefront without a step of its own
+  // (a split of fewer than four steps) re-reads the split's last step and never uses it.  With
+  // the number of loads in flight known, the store of the queries below waits for the queries
+  // only, and the barrier after it no longer ties the four wavefronts to the slowest first step.
+  load_k_at(s < nsteps ? s : nsteps - 1);
+  load_v_at(s < nsteps ? s : nsteps - 1);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj) *(u32x4*)(qs + (2 * wv + jj) * 1024 + lane * 16) = qtmp[jj];
   if (fold && !early) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
-      if (row_mine[t]) store_row(rows[t], row_slot[t], (char*)a.layer_base, tid);
+      if (row_mine[t])
+        store_row(rows[t], __builtin_amdgcn_readlane(slot2, t), (char*)a.layer_base, tid);
   }
   __syncthreads();
   const char* qf = qs + lane * 16;
