@@ -675,6 +675,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       struct Rec {
         int64_t key;     // readers of shared pages: (table, split begin); others: unique
         int32_t idx, cost;
+        bool tile;
       };
       std::vector<Rec> recs(nw);
       for (int32_t i = 0; i < nw; ++i) {
@@ -685,6 +686,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         const bool shares = tile || !(r[oxy::W_PATH] & oxy::kPathAppends);
         recs[i].idx = i;
         recs[i].cost = tile ? 2 * steps : steps;
+        recs[i].tile = tile;
         recs[i].key = shares ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
                              : -(int64_t)i - 1;
       }
@@ -700,6 +702,14 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         int32_t j = i;
         int64_t cst = 0;
         while (j < nw && recs[j].key == recs[i].key) cst += recs[j++].cost;
+        // A tile that is the only reader of its pages fetches all of them from HBM itself (a
+        // tile that shares its split finds most of them on their way into the L2 already) and
+        // is the slowest kind of work item per step: it counts half as much again, which makes
+        // the pairing below give it the smallest partner on its CU, or none.
+        if (j - i == 1 && recs[i].tile) {
+          recs[i].cost = recs[i].cost * 3 / 2;
+          cst = recs[i].cost;
+        }
         grps.push_back({i, j - i, cst});
         i = j;
       }
@@ -710,9 +720,17 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       int64_t qcost[kXcd] = {0};
       for (int x = 0; x < kXcd; ++x) queue[x].reserve(nw / kXcd + 16);
       for (const Grp& g : grps) {
-        int best = 0;
-        for (int x = 1; x < kXcd; ++x)
-          if (qcost[x] < qcost[best]) best = x;
+        // least loaded XCD among those that still have a resident slot for every record of the
+        // group (two workgroups on each of 32 CUs); any XCD if none has
+        int best = -1;
+        for (int x = 0; x < kXcd; ++x)
+          if (queue[x].size() + g.count <= (size_t)2 * kCuPerXcd && (best < 0 || qcost[x] < qcost[best]))
+            best = x;
+        if (best < 0) {
+          best = 0;
+          for (int x = 1; x < kXcd; ++x)
+            if (qcost[x] < qcost[best]) best = x;
+        }
         queue[best].insert(queue[best].end(), recs.begin() + g.first,
                            recs.begin() + g.first + g.count);
         qcost[best] += g.cost;
