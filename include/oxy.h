@@ -223,7 +223,7 @@ int32_t oxy_mixed_attention_static(oxy_pool *pool, const oxy_batch *batch, int32
  * a decode item's new token is read only by the work item that owns the last split of its own
  * history, so that work item writes it first; an item whose own history was empty before the
  * step (an action chunk, Sec. 3.2: its K/V live for one denoise step) reads its keys from
- * k_new / v_new directly and writes them to the pool on the side.  Outputs and pool contents
+ * k_new / v_new directly (the layer's merge launch writes them to the pool).  Outputs and pool contents
  * are those of flags = 0.  A batch with an item of more than 2 new tokens on a non-empty own
  * history is not covered; for it the flag is ignored.  Wins over OXY_STEP_FUSE_ACROSS_LAYERS.
  * OXY_STEP_GRAPH (with any of the above) = the launches of the step are recorded into a HIP graph

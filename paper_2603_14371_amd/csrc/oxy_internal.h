@@ -64,7 +64,7 @@ struct AttnArgs {
   // Append folded into the work items (all three null otherwise): this step's new rows
   // [n_q][256] bf16 and their slots.  A streaming work item first writes the new rows that lie
   // in its key range into the pool; a fresh tile reads its keys from the new rows themselves
-  // and the tile of split 0 writes its own query tokens' rows.
+  // (the merge launch of the layer writes those rows to the pool).
   const void* k_new;
   const void* v_new;
   const int32_t* d_slots;
@@ -84,6 +84,7 @@ struct AppendArgs {
   const int32_t* d_slots;
   int32_t n_tokens;
   void* layer_base;
+  const int32_t* tok_list;   // null: tokens 0..n_tokens-1; else the n_tokens token ids to append
 };
 // merge of `a`, and in the same launch the append described by `next` (may be null)
 hipError_t launch_merge_append(const AttnArgs& a, const AppendArgs* next, hipStream_t s,

@@ -342,6 +342,8 @@ __device__ __forceinline__ int block_of(const SplitIds& ids, const int pi) {
 // LDS (double-buffered, one barrier per 32-key step) and own 16 rows each.
 // kFresh: the keys are rows of this step's k_new / v_new (row0 + own position) instead of pool
 // pages; they are brought into the same register image, so everything after the fetch is shared.
+// The pool receives those rows from the merge launch of the same layer (nothing reads them from
+// the pool during this launch, and the tiles are the last workgroups of a small launch to end).
 template <bool kFresh>
 __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi, char* smem,
                                           const int row0) {
@@ -532,25 +534,6 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     commit((s + 1) & 1, nxt);
     __syncthreads();
   };
-  // kFresh: the pool still has to receive the rows; the tile of split 0 writes its own query
-  // tokens'.  All eight rows are loaded first (the record repeats the last token id for a
-  // short tile), the stores follow once the first pages have been waited for anyway.
-  RowPart rows[kFresh ? 8 : 1];
-  int32_t slot8 = 0;   // lane j % 8: pool slot of the record's token j
-  const bool writes_rows = kFresh && wi.kv_begin == 0;
-  if constexpr (kFresh) {
-    // loaded by every fresh tile, stored only by the tile of split 0: loads under a condition
-    // would be waited for where the paths meet, in front of the queries and the first keys
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const int tk = __builtin_amdgcn_readlane(wi.rec, 8 + t);
-      rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
-                         (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
-    }
-    // one load per lane instead of one wave-uniform load per token: a uniform value is wanted
-    // in a scalar register, i.e. waited for right where it is loaded
-    slot8 = a.d_slots[__shfl(wi.rec, 8 + (lane & 7))];
-  }
   {  // the query rows are requested first: loads complete in order per wavefront, and the
      // first product should wait for step 0 only, not for step 1 as well
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
@@ -583,14 +566,6 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   __builtin_amdgcn_sched_barrier(0);
   sanitize(0, st0);
   commit(0, st0);
-  if constexpr (kFresh) {
-    if (writes_rows) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if (t < wi.n_tok)
-          store_row(rows[t], __builtin_amdgcn_readlane(slot8, t), (char*)a.layer_base, tid);
-    }
-  }
   __syncthreads();
   for (int s = 0; s < nsteps; s += 2) {   // steps in pairs; a step past the end moves dummies
     body(s, st0, st1);
@@ -944,14 +919,16 @@ __device__ __forceinline__ void merge_block(const AttnArgs& a, const int tok) {
 
 __global__ __launch_bounds__(256) void merge_kernel(const AttnArgs a) { merge_block(a, blockIdx.x); }
 
-// merge of one layer and, in the same launch, the append of the next layer's new rows (the two
-// touch disjoint memory: partials/outputs of layer l, pool slots of layer l+1)
+// merge of one layer and, in the same launch, an append that touches other memory than the
+// merge: the next layer's new rows (cross-layer fusion), or this layer's rows of the items whose
+// tiles read their keys from k_new / v_new (nx.tok_list names their tokens)
 __global__ __launch_bounds__(256) void merge_append_kernel(const AttnArgs a, const AppendArgs nx) {
   const int n_merge = a.n_q;
   if ((int)blockIdx.x < n_merge) {
     merge_block(a, blockIdx.x);
   } else {
-    const int tok = blockIdx.x - n_merge;
+    const int i = blockIdx.x - n_merge;
+    const int tok = nx.tok_list ? nx.tok_list[i] : i;
     append_row((const uint16_t*)nx.k_new + (size_t)tok * kDim,
                (const uint16_t*)nx.v_new + (size_t)tok * kDim, nx.d_slots[tok],
                (char*)nx.layer_base, threadIdx.x);

@@ -66,21 +66,21 @@ struct StepKey {
   size_t kv_stride = 0, q_stride = 0, lse_stride = 0;
   float scale = 0.f;
   int32_t layer_begin = 0, layer_end = 0, mode = 0;   // mode: 0 separate, 1 fused, 2 folded
-  int32_t n_work = 0, n_tokens = 0, off_work = 0, off_tables = 0, off_part_off = 0,
+  int32_t n_work = 0, n_tokens = 0, n_fresh = 0, off_work = 0, off_tables = 0, off_part_off = 0,
           off_n_parts = 0;
   bool operator==(const StepKey& o) const {
     return d_base == o.d_base && k_new == o.k_new && v_new == o.v_new && q == o.q &&
            out == o.out && lse == o.lse && kv_stride == o.kv_stride && q_stride == o.q_stride &&
            lse_stride == o.lse_stride && scale == o.scale && layer_begin == o.layer_begin &&
            layer_end == o.layer_end && mode == o.mode && n_work == o.n_work &&
-           n_tokens == o.n_tokens && off_work == o.off_work && off_tables == o.off_tables &&
+           n_tokens == o.n_tokens && n_fresh == o.n_fresh && off_work == o.off_work && off_tables == o.off_tables &&
            off_part_off == o.off_part_off && off_n_parts == o.off_n_parts;
   }
   // same number and kinds of launches in the same order: an instantiated graph can be updated
   // in place from a recording of the other
   bool same_topology(const StepKey& o) const {
     return layer_end - layer_begin == o.layer_end - o.layer_begin && mode == o.mode &&
-           (n_tokens > 0) == (o.n_tokens > 0);
+           (n_tokens > 0) == (o.n_tokens > 0) && (n_fresh > 0) == (o.n_fresh > 0);
   }
 };
 struct StepGraph {
@@ -120,6 +120,8 @@ struct oxy_batch {
   int32_t flags = 0;
   int32_t n_items = 0, n_tokens = 0, n_work = 0, n_partials = 0;
   int32_t n_launch = 0;   // n_work rounded up to a multiple of 64 with padding records: the grid
+  int32_t n_fresh = 0;    // tokens of items whose own-phase tiles read k_new / v_new (folded append)
+  int32_t off_fresh = 0;
   bool append_foldable = false;   // every item has <= 2 new tokens or an empty own history
   // word offsets inside the descriptor
   int32_t off_slots = 0, off_work = 0, off_toks = 0, off_tables = 0, off_part_off = 0,
@@ -168,7 +170,7 @@ size_t table_words_of(const oxy_pool_config& c) { return 2 * (size_t)c.num_block
 size_t desc_words_of(const oxy_pool_config& c) {
   return (size_t)c.max_append_tokens + (size_t)oxy::kWorkWords * c.max_work_items +
          2 * (size_t)c.max_q_tokens /* token lists */ + table_words_of(c) /* tables */ +
-         2 * (size_t)c.max_q_tokens /* part_off, n_parts */;
+         3 * (size_t)c.max_q_tokens /* part_off, n_parts, fresh tokens */;
 }
 
 void layout_of(const oxy_pool_config& c, size_t* acc_off, size_t* ml_off, size_t* total) {
@@ -545,6 +547,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   // kept as their eight header words until the order is known.
   constexpr int kHdr = 8;
   std::vector<int32_t> hdr, toks, n_parts(append_only ? 0 : n_tokens, 0);
+  std::vector<int32_t> fresh_toks;   // tokens whose rows the merge launch writes under a folded append
   struct TableRef {
     int32_t off;
     const std::vector<int32_t>* src;
@@ -644,8 +647,10 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
       const bool causal = pl.s->kind == OXY_KIND_DECODE;
       int32_t path = n_new <= 2 ? (oxy::PATH_STREAM | oxy::kPathAppends) : oxy::PATH_TILE;
       if ((path & oxy::kPathMask) == oxy::PATH_TILE) {
-        if (pl.old_len == 0)
+        if (pl.old_len == 0) {
           path |= oxy::kPathFresh | (pl.tok0 << oxy::kPathRowShift);
+          for (int32_t t = 0; t < n_new; ++t) fresh_toks.push_back(pl.tok0 + t);
+        }
         else
           foldable = false;   // old and new keys in one tile: only the separate append covers it
       }
@@ -809,7 +814,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   b->n_partials = (int32_t)n_partials;
   b->off_slots = 0;
   b->append_foldable = foldable;
-  // Sections in the order slots | work | part_off | n_parts | token lists | tables: the block
+  // Sections in the order slots | work | part_off | n_parts | fresh tokens | token lists | tables: the block
   // tables, whose size changes whenever a stream takes a new block, come last, so that the
   // device addresses of all sections stay the same from step to step while the shape of the
   // batch (tokens, work items, tile token lists) does -- a recorded launch sequence
@@ -821,7 +826,9 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   b->off_work = b->off_slots + (int32_t)n_tokens;
   b->off_part_off = b->off_work + b->n_launch * oxy::kWorkWords;
   b->off_n_parts = b->off_part_off + (int32_t)part_off.size();
-  b->off_toks = b->off_n_parts + (int32_t)n_parts.size();
+  b->n_fresh = (int32_t)fresh_toks.size();
+  b->off_fresh = b->off_n_parts + (int32_t)n_parts.size();
+  b->off_toks = b->off_fresh + b->n_fresh;
   b->off_tables = b->off_toks + (int32_t)toks.size();
   std::vector<int32_t>& h = b->host;
   h.resize((size_t)b->off_tables + tbl_words);
@@ -847,6 +854,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
   for (const TableRef& tr : table_refs)
     std::copy(tr.src->begin(), tr.src->begin() + tr.count, tables + tr.off);
   std::copy(toks.begin(), toks.end(), h.begin() + b->off_toks);
+  std::copy(fresh_toks.begin(), fresh_toks.end(), h.begin() + b->off_fresh);
   std::copy(part_off.begin(), part_off.end(), h.begin() + b->off_part_off);
   std::copy(n_parts.begin(), n_parts.end(), h.begin() + b->off_n_parts);
   // Work records, 128 bytes each: header, then inline copies of the tile's token ids and of the
@@ -1011,6 +1019,7 @@ int32_t issue_step(const StepCall& c, hipStream_t s) {
     ap.d_slots = d_desc + b->off_slots;
     ap.n_tokens = b->n_tokens;
     ap.layer_base = layer_base(p, layer);
+    ap.tok_list = nullptr;
     return ap;
   };
   auto append_now = [&](int32_t layer) {
@@ -1047,6 +1056,12 @@ int32_t issue_step(const StepCall& c, hipStream_t s) {
     if (c.fuse && layer + 1 < c.layer_end) {
       oxy::AppendArgs nx = append_of(layer + 1);
       e = oxy::launch_merge_append(a, &nx, s, ev[2], ev[3]);
+    } else if (c.fold && b->n_fresh > 0) {
+      // items whose tiles took their keys from k_new / v_new: their rows go to the pool here
+      oxy::AppendArgs fr = append_of(layer);
+      fr.n_tokens = b->n_fresh;
+      fr.tok_list = d_desc + b->off_fresh;
+      e = oxy::launch_merge_append(a, &fr, s, ev[2], ev[3]);
     } else {
       e = oxy::launch_merge_append(a, nullptr, s, ev[2], ev[3]);
     }
@@ -1079,6 +1094,7 @@ int32_t replay_step(const StepCall& c, hipStream_t s) {
   key.mode = c.fold ? 2 : c.fuse ? 1 : 0;
   key.n_work = b->n_launch;
   key.n_tokens = b->n_tokens;
+  key.n_fresh = b->n_fresh;
   key.off_work = b->off_work;
   key.off_tables = b->off_tables;
   key.off_part_off = b->off_part_off;
