@@ -655,7 +655,11 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
           foldable = false;   // old and new keys in one tile: only the separate append covers it
       }
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok_for(pl.new_len);
-      const int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
+      int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
+      // A short chunk on an empty history (an action chunk, Sec. 3.2) is cut into single 32-key
+      // steps: its tiles start last (their keys are this step's new rows) and would otherwise
+      // be the workgroups the launch ends with.  Depends on the item alone, like every split.
+      if (n_new > 2 && pl.old_len == 0 && pl.new_len <= 64 && !c.split_tokens) split = 32;
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
         const int32_t n = std::min(step_tok, n_new - t0);
         const int32_t tok_off = (int32_t)toks.size();
