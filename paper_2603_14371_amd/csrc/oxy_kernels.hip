@@ -76,6 +76,25 @@ __device__ __forceinline__ float row_max4(float x) {
   const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
+// sum over the same four lanes, same two swaps: every lane adds its own value and its partner's
+__device__ __forceinline__ float row_sum4(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const uint32_t v = __float_as_uint(y);
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+// max over the 16 lanes of a row (lanes 16r .. 16r+15): four DPP moves, no LDS round trip.
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror: after each step twice
+// as many neighbouring lanes hold the same value, so the mirrors act like xor 4 and xor 8.
+__device__ __forceinline__ float lanes16_max(float x) {
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0xB1, 0xF, 0xF, true)));
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x4E, 0xF, 0xF, true)));
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x141, 0xF, 0xF, true)));
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x140, 0xF, 0xF, true)));
+  return x;
+}
 
 // ------------------------------------------------------------------------------------------
 // page layout (see oxy.h)
@@ -278,8 +297,12 @@ __device__ __forceinline__ void softmax_step(const f32x4 s0, const f32x4 s1, con
     const float m_new = grow ? mx : m;
     const float alpha = grow ? fast_exp2(m - m_new) : 1.f;   // m = -inf gives 0
     l *= alpha;
+    // a wavefront whose rows have seen no finite logit yet (the first step of every work item)
+    // holds zeros: scaling them changes nothing
+    if (__any(m != ninf)) {
 #pragma unroll
-    for (int c = 0; c < 16; ++c) acc[c] *= alpha;
+      for (int c = 0; c < 16; ++c) acc[c] *= alpha;
+    }
     m = m_new;
   }
   const float m_use = (m == ninf) ? 0.f : m;
@@ -318,8 +341,8 @@ struct WorkItem {
   int rec;   // this lane's word of the 32-word record (lanes 32..63 mirror 0..31)
 };
 
-// Block ids of the split, one per lane: the first 16 pages from the record's inline copy (no
-// dependent load), all pages (a split has at most 64) from the block table.  The table load is
+// Block ids of the split, one per lane: the first 16 pages are words 16..31 of the record itself
+// (no dependent load), all pages (a split has at most 64) come from the block table.  The table load is
 // issued whether or not the split has more than 16 pages: a load under a condition would make
 // the compiler wait for EVERYTHING in flight wherever the two paths meet again (it counts
 // outstanding loads per control-flow path), and that wait would sit in front of the first pages.
@@ -328,13 +351,13 @@ struct SplitIds {
 };
 __device__ __forceinline__ SplitIds split_block_ids(const WorkItem& wi, const int lane, const int npg) {
   SplitIds ids;
-  ids.lo = __shfl(wi.rec, 16 + (lane & 15));
+  ids.lo = wi.rec;
   ids.hi = wi.tbl[(wi.kv_begin >> 4) + (lane < npg ? lane : npg - 1)];
   return ids;
 }
 // pi is wave-uniform
 __device__ __forceinline__ int block_of(const SplitIds& ids, const int pi) {
-  return pi < kWorkInlinePages ? __builtin_amdgcn_readlane(ids.lo, pi)
+  return pi < kWorkInlinePages ? __builtin_amdgcn_readlane(ids.lo, 16 + pi)
                                : __builtin_amdgcn_readlane(ids.hi, pi);
 }
 
@@ -353,11 +376,17 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   const int ts = 2 * wv + (n >> 3), h = n & 7;
   const bool row_valid = ts < wi.n_tok;
   const bool wave_active = 2 * wv < wi.n_tok;
-  const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
+  // token ids sit in words 8..15 of the record: this wavefront's two, and the tile's first for
+  // rows past its tokens (wave-uniform lane reads instead of a shuffle through LDS)
+  const int tok_a = __builtin_amdgcn_readlane(wi.rec, 8 + 2 * wv);
+  const int tok_b = __builtin_amdgcn_readlane(wi.rec, 9 + 2 * wv);
+  const int tok_z = __builtin_amdgcn_readlane(wi.rec, 8);
+  const int tok = row_valid ? ((n >> 3) ? tok_b : tok_a) : tok_z;
   const int qpos = wi.q0 + ts;
-  // first partial slot of this row's token: needed only at the end, loaded now so that the
-  // epilogue does not wait for it
-  const int part_base = a.part_off[tok];
+  // first partial slot of this wavefront's two tokens (words past the tile's tokens repeat its
+  // last one): needed only at the end, loaded now (two scalar loads) so that the epilogue does
+  // not wait for them
+  const int part_a = a.part_off[tok_a] + wi.part_idx, part_b = a.part_off[tok_b] + wi.part_idx;
   u32x4 qf[8];
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
@@ -513,6 +542,15 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       s0 = mfma16(*(const u32x4*)(sk + lds_k + j * 1024), qf[j], s0);
       s1 = mfma16(*(const u32x4*)(sk + lds_k + j * 1024 + 512), qf[j], s1);
     }
+    // eight operand reads ahead of the products: left to itself the compiler keeps two in
+    // flight, and every product then waits a full LDS round trip
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     u32x4 pf, pl;
     softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
                  pf, pl);
@@ -521,6 +559,13 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       const u32x4 v = *(const u32x4*)(sk + lds_v + c * 512);
       acc[c] = mfma16(v, pl, mfma16(v, pf, acc[c]));
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);   // as above: eight reads ahead
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 1);
   };
   // body(s, cur, nxt): cur's content (step s) already sits in LDS, nxt holds step s+1 in
   // flight.  The scheduling barriers keep the order "issue s+2, compute s, then wait for s+1",
@@ -571,8 +616,7 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     body(s, st0, st1);
     body(s + 1, st1, st0);
   }
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
+  l = row_sum4(l);
   // The partial leaves as (m, l, scale, acc / scale in fp16): half the bytes of fp32, and the
   // per-row scale (max |acc| of the row) keeps it independent of the magnitude of the values.
   float amax = 0.f;
@@ -595,13 +639,13 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     *(u32x2*)(ep + n * kEpilogueStride + (16 * c + 4 * g) * 2) = v;
   }
   asm volatile("" ::: "memory");   // the reads below are of another type: keep them behind the writes
-  const int slot_lane = part_base + wi.part_idx;   // of this lane's row n
+  const int slot_lane = (n >> 3) ? part_b : part_a;   // of this lane's row n
   if (row_valid && g == 0)
     *(f32x4*)(a.part_ml + ((size_t)slot_lane * kHeads + h) * 4) = (f32x4){m, l, amax, 0.f};
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = 2 * it + (lane >> 5);              // row of this wavefront's 16
-    const int slot_row = __shfl(slot_lane, row);       // lane `row` (g = 0) owns that row
+    const int slot_row = (it >> 2) ? part_b : part_a;  // rows 0..7: first token, 8..15: second
     const u32x4 v = *(const u32x4*)(ep + row * kEpilogueStride + (lane & 31) * 16);
     if (2 * wv + (row >> 3) < wi.n_tok)
       *(u32x4*)(a.part_acc + ((size_t)slot_row * kHeads + (row & 7)) * kDim + (lane & 31) * 8) = v;
@@ -623,11 +667,12 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
   const int n = lane & 15, g = lane >> 4;
   const int ts = n >> 3, h = n & 7;
   const bool row_valid = ts < wi.n_tok;
-  const int tok = __shfl(wi.rec, 8 + (row_valid ? ts : 0));
+  const int tok_a = __builtin_amdgcn_readlane(wi.rec, 8), tok_b = __builtin_amdgcn_readlane(wi.rec, 9);
+  const int tok = (row_valid && ts) ? tok_b : tok_a;
   const int qpos = wi.q0 + ts;
   // In the epilogue thread tid writes 16 dims of row tid / 16; the first partial slot of that
   // row's token is loaded now so that the epilogue does not wait for it.
-  const int otok = __shfl(wi.rec, 8 + ((tid >> 7) < wi.n_tok ? (tid >> 7) : 0));
+  const int otok = ((wv >> 1) && wi.n_tok > 1) ? tok_b : tok_a;
   const int part_base = a.part_off[otok];
   float m = -__builtin_inff(), l = 0.f;
   f32x4 acc[16];
@@ -695,7 +740,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       rows[t] = load_row((const uint16_t*)a.k_new + (size_t)tk * kDim,
                          (const uint16_t*)a.v_new + (size_t)tk * kDim, tid);
     }
-    slot2 = a.d_slots[__shfl(wi.rec, 8 + (lane & 1))];   // per lane: see the fresh tiles
+    slot2 = a.d_slots[(lane & 1) ? tok_b : tok_a];   // one load per lane, read with v_readlane
     const int first_new = (max(pos0, wi.kv_begin) - wi.kv_begin) >> 5;
     early = first_new < 4;
     if (early) {
@@ -748,6 +793,14 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       s0 = mfma16(kr[2 * j], q, s0);
       s1 = mfma16(kr[2 * j + 1], q, s1);
     }
+    // four query reads ahead of the products (see the tile path)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 2);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 2);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 2);
     u32x4 pf, pl;
     softmax_step(s0, s1, left < 32 || pos + 31 > wi.q0, pos, wi.kv_end, qpos, g, sl2, m, l, acc,
                  pf, pl);
@@ -766,8 +819,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
     load_v(s + 4);
     __builtin_amdgcn_sched_barrier(0);
   }
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
+  l = row_sum4(l);
   // combine the four wavefronts' results (log-sum-exp rule) and write one partial
   float* sm = (float*)smem;
 #pragma unroll
@@ -810,8 +862,7 @@ __device__ __forceinline__ void stream_path(const AttnArgs& a, const WorkItem& w
       for (int e = 0; e < 4; ++e) amax = fmaxf(amax, fabsf(o[q][e]));
     }
     // row scale over the 16 threads that hold this row (the branch is uniform per wavefront)
-#pragma unroll
-    for (int sh = 1; sh < 16; sh <<= 1) amax = fmaxf(amax, __shfl_xor(amax, sh));
+    amax = lanes16_max(amax);
     const float inv = amax > 0.f ? 1.f / amax : 0.f;
     const u32x4 lo = {pack_f16(o[0][0] * inv, o[0][1] * inv), pack_f16(o[0][2] * inv, o[0][3] * inv),
                       pack_f16(o[1][0] * inv, o[1][1] * inv), pack_f16(o[1][2] * inv, o[1][3] * inv)};
