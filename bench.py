@@ -259,20 +259,23 @@ def bench_stress(args, device, workload=None, alt_schedules=True):
     return res
 
 
-def bench_sweep(args, device, counts=(64, 128, 256, 512), splits=((0, 0), (512, 512))):
+def bench_sweep(args, device, series=((0, 0, (64, 128, 256, 512)), (512, 512, (64, 128, 256, 512)),
+                                      (1024, 1024, (512, 1024, 2048)))):
     """The stress geometry at growing stream counts (groups of 8 streams per 2048-token prefix,
     own histories ~U{1..2048}, two action chunks): where the work-item kernel gets to on the
     HBM roofline as a launch grows.  The number of layers shrinks as the streams grow so that
     every point cycles through at least ~1.5 GB of distinct KV (the memory-side cache holds
-    256 MB) without filling the card.  Two series: the default split sizes of the pool (256
-    tokens per work item on these lengths, what the 64-stream launch needs to fill the chip)
-    and 512-token work items (pool configuration split_tokens = stream_split_tokens = 512), which
-    pay off once a launch has several times more work items than the chip holds at once."""
+    256 MB) without filling the card.  Three series (split_tokens, stream_split_tokens, stream
+    counts): the default split sizes of the pool (256 tokens per work item on these lengths, what
+    the 64-stream launch needs to fill the chip), 512-token work items, which pay off once a
+    launch has several times more work items than the chip holds at once, and 1024-token work
+    items (the largest the pool accepts) on launches of 0.7 to 2.7 GB: the rate the kernel
+    settles at when the fixed cost of a launch no longer counts."""
     import argparse as _ap
     import torch
     from paper_2603_14371_amd import synth
     out = []
-    for split, stream_split in splits:
+    for split, stream_split, counts in series:
         for n in counts:
             layers = max(3, -(-18 * 64 // n))
             blocks = 8192 * n // 64
@@ -837,7 +840,7 @@ def main():
     ap.add_argument("--no-alt-schedules", action="store_true",
                     help="profiling aid: skip the passes with the other launch schedules")
     ap.add_argument("--sweep-streams", action="store_true",
-                    help="run only the stream-count sweep (64..512 streams, stress geometry)")
+                    help="run only the stream-count sweep (64..2048 streams, stress geometry)")
     ap.add_argument("--only-stress", action="store_true",
                     help="profiling aid: the stress section only")
     ap.add_argument("--only-action", action="store_true",

@@ -579,8 +579,7 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     commit((s + 1) & 1, nxt);
     __syncthreads();
   };
-  {  // the query rows are requested first: loads complete in order per wavefront, and the
-     // first product should wait for step 0 only, not for step 1 as well
+  auto load_q = [&]() {
     const char* qrow = (const char*)a.q + ((size_t)tok * kHeads + h) * (kDim * 2);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -590,13 +589,17 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
       const u32x4 x = *(const u32x4*)(qrow + j * 64 + g * 16);
       qf[j] = row_valid ? x : z;
     }
-  }
-  __builtin_amdgcn_sched_barrier(0);
+  };
   if constexpr (kFresh) {
-    // every load of steps 0 and 1 goes out before the first transpose waits for its rows
+    // Step 0 first: its rows have to pass through the transpose, LDS and a barrier before the
+    // first product, the query rows only have to be in registers by then.  Every load of steps
+    // 0 and 1 goes out before the first transpose waits for its rows.
     u32x2 r0[8], r1[8];
     fetch_fresh_k(0, st0);
     fresh_v_load(0, r0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_q();
+    __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 1) {
       fetch_fresh_k(1, st1);
       fresh_v_load(1, r1);
@@ -605,6 +608,10 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     fresh_v_assemble(r0, st0);
     if (nsteps > 1) fresh_v_assemble(r1, st1);
   } else {
+    // the query rows are requested first: loads complete in order per wavefront, and the
+    // first product should wait for step 0 only, not for step 1 as well
+    load_q();
+    __builtin_amdgcn_sched_barrier(0);
     fetch(0, st0);
     fetch(1, st1);
   }
