@@ -64,6 +64,25 @@ def test_folded_append_two_token_decode_across_a_split_boundary_and_fallback():
     _same_bits(g_sep, g_fold)
 
 
+@pytest.mark.parametrize("chunk", [31, 33, 50, 64, 65])
+def test_chunks_around_the_single_step_rule(chunk):
+    """A chunk of at most 64 tokens on an empty history is evaluated in single 32-key steps (one
+    or two split results per token), a longer one in the pool's usual splits; both next to a
+    decode item, with the pool's default split sizes, in both append modes."""
+    from paper_2603_14371_amd.synth import _TraceBuilder, _workload, DECODE, ACTION
+    b = _TraceBuilder()
+    pid = b.prefix(200)
+    d0, a0, a1 = b.stream(pid, DECODE), b.stream(pid, ACTION), b.stream(-1, ACTION)
+    b.step([(d0, 1), (a0, chunk), (a1, chunk)])
+    b.step([(d0, 2), (a0, chunk)])
+    w = _workload("chunk_rule", 4100 + chunk, 2, 96, b.trace)
+    gw, g_fold, ow, _ = run_both(w, poison=True, fold_append=True)
+    _finish(gw, ow)
+    gw, g_sep, ow, _ = run_both(w, poison=True)
+    _finish(gw, ow)
+    _same_bits(g_sep, g_fold)
+
+
 def test_folded_append_reduced_stress_every_item():
     w = synth.stress(n_layers=2, n_streams=16, group=4, prefix_len=300, hist_hi=400,
                      num_blocks=2048, churn_ops=300, mixed_steps=2)
