@@ -121,7 +121,8 @@ typedef struct {
                                tokens, streamed token pairs on a shorter one) and the own phase of
                                action chunks and multi-token decode.  Multiple of 32, <= 1024.
                                0 -> chosen from the length of the KV source alone: about an
-                               eighth of it, within [64, 256]                                */
+                               eighth of it, within [64, 256]; 32 for a chunk of at most 64
+                               tokens on an empty own history (an action chunk)             */
   int32_t stream_split_tokens; /* KV tokens per work item of the decode streaming path, multiple
                                of 32, <= 1024 (0 -> split_tokens, or 256 if that is 0).  Both depend
                                only on the pool and the item, so an item's arithmetic never
