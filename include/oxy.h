@@ -124,7 +124,8 @@ typedef struct {
                                eighth of it, within [64, 256]; 32 for a chunk of at most 64
                                tokens on an empty own history (an action chunk)             */
   int32_t stream_split_tokens; /* KV tokens per work item of the decode streaming path, multiple
-                               of 32, <= 1024 (0 -> split_tokens, or 256 if that is 0).  Both depend
+                               of 32, <= 1024 (0 -> split_tokens; if that is 0 too: 128 for an own
+                               history of at most 512 tokens, else 256).  Both depend
                                only on the pool and the item, so an item's arithmetic never
                                depends on its batch mates                                    */
   int32_t flags;

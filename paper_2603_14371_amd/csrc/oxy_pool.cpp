@@ -149,14 +149,16 @@ bool resolve_config(const oxy_pool_config* in, oxy_pool_config* c) {
   if (c->max_partials == 0) c->max_partials = 32 * c->max_q_tokens;
   // split_tokens == 0 stays 0: the tile path then sizes its splits from the length of the KV
   // source alone (see tile_split_for), which keeps an item's arithmetic independent of its batch
-  if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens ? c->split_tokens : 256;
+  // stream_split_tokens == 0 becomes split_tokens; both 0: by the item's length (stream_split_for)
+  if (c->stream_split_tokens == 0) c->stream_split_tokens = c->split_tokens;
   // query token ids travel in 23 bits of a work-record word (kPathRowShift)
   if (c->max_q_tokens > (1 << 20) || c->max_append_tokens > (1 << 26)) return false;
   if (c->max_live_batches < 1 || c->max_live_batches > 64 || c->max_q_tokens < 1 ||
       c->max_append_tokens < 1 || c->max_work_items < 1 || c->max_partials < 1 ||
       (c->split_tokens != 0 && (c->split_tokens < 32 || c->split_tokens % 32 != 0)) ||
       c->split_tokens > 1024 ||
-      c->stream_split_tokens < 32 || c->stream_split_tokens % 32 != 0 ||
+      (c->stream_split_tokens != 0 &&
+       (c->stream_split_tokens < 32 || c->stream_split_tokens % 32 != 0)) ||
       c->stream_split_tokens > 1024)
     return false;
   return true;
@@ -202,6 +204,15 @@ int32_t tile_split_for(const oxy_pool_config& c, int32_t len) {
   if (c.split_tokens) return c.split_tokens;
   int32_t s = ((len + 7) / 8 + 31) / 32 * 32;
   return std::max(64, std::min(256, s));
+}
+
+// Streaming path on an item's own history.  A history of at most 512 tokens is cut into
+// 128-token work items (one step per wavefront: steps that wait for memory one after the other
+// are what such a launch is made of), a longer one into 256-token work items (two steps per
+// wavefront; halves the work items and split results of a launch that is bound by bytes).
+int32_t stream_split_for(const oxy_pool_config& c, int32_t len) {
+  if (c.stream_split_tokens) return c.stream_split_tokens;
+  return len <= 512 ? 128 : 256;
 }
 
 char* layer_base(const oxy_pool* p, int32_t layer) {
@@ -655,7 +666,7 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
           foldable = false;   // old and new keys in one tile: only the separate append covers it
       }
       const int32_t step_tok = n_new <= 2 ? 2 : tile_tok_for(pl.new_len);
-      int32_t split = n_new <= 2 ? c.stream_split_tokens : tile_split_for(c, pl.new_len);
+      int32_t split = n_new <= 2 ? stream_split_for(c, pl.new_len) : tile_split_for(c, pl.new_len);
       // A short chunk on an empty history (an action chunk, Sec. 3.2) is cut into single 32-key
       // steps: its tiles start last (their keys are this step's new rows) and would otherwise
       // be the workgroups the launch ends with.  Depends on the item alone, like every split.
@@ -691,11 +702,14 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         const int32_t* r = &hdr[(size_t)i * kHdr];
         const int32_t steps = (r[oxy::W_KV_END] - r[oxy::W_KV_BEGIN] + 31) / 32;
         const bool tile = (r[oxy::W_PATH] & oxy::kPathMask) == oxy::PATH_TILE;
-        // work items that read pages others read too: tiles, and streaming items on prefix pages
-        const bool shares = tile || !(r[oxy::W_PATH] & oxy::kPathAppends);
+        // work items that read pages others read too: tiles (not those that take their keys from
+        // the step's new rows: they read no pages, and dealt out as one group they would sit two
+        // to a CU on one XCD), and streaming items on prefix pages
+        const bool fresh = (r[oxy::W_PATH] & oxy::kPathFresh) != 0;
+        const bool shares = fresh ? false : (tile || !(r[oxy::W_PATH] & oxy::kPathAppends));
         recs[i].idx = i;
         recs[i].cost = tile ? 2 * steps : steps;
-        recs[i].tile = tile;
+        recs[i].tile = tile && !fresh;
         recs[i].key = shares ? (((int64_t)r[oxy::W_TBL_OFF] << 32) | (uint32_t)r[oxy::W_KV_BEGIN])
                              : -(int64_t)i - 1;
       }
