@@ -575,8 +575,10 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
     __builtin_amdgcn_sched_barrier(0);
     if (wave_active && s < nsteps) compute(s);
     __builtin_amdgcn_sched_barrier(0);
-    sanitize(s + 1, nxt);
-    commit((s + 1) & 1, nxt);
+    if (s + 1 < nsteps) {   // after the last step only the barrier is left: the epilogue reuses LDS
+      sanitize(s + 1, nxt);
+      commit((s + 1) & 1, nxt);
+    }
     __syncthreads();
   };
   auto load_q = [&]() {
@@ -619,9 +621,9 @@ __device__ __forceinline__ void tile_path(const AttnArgs& a, const WorkItem& wi,
   sanitize(0, st0);
   commit(0, st0);
   __syncthreads();
-  for (int s = 0; s < nsteps; s += 2) {   // steps in pairs; a step past the end moves dummies
+  for (int s = 0; s < nsteps; s += 2) {   // steps in pairs: the two register stages swap roles
     body(s, st0, st1);
-    body(s + 1, st1, st0);
+    if (s + 1 < nsteps) body(s + 1, st1, st0);
   }
   l = row_sum4(l);
   // The partial leaves as (m, l, scale, acc / scale in fp16): half the bytes of fp32, and the

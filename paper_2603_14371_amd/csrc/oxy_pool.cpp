@@ -665,12 +665,15 @@ int32_t oxy_batch_build(oxy_pool* p, const oxy_item* items, int32_t n_items, int
         else
           foldable = false;   // old and new keys in one tile: only the separate append covers it
       }
-      const int32_t step_tok = n_new <= 2 ? 2 : tile_tok_for(pl.new_len);
+      // a short chunk on an empty history (see below): single 32-key steps, so all four
+      // wavefronts of a tile get rows (8 tokens) -- half as many workgroups to place
+      const bool short_chunk = n_new > 2 && pl.old_len == 0 && pl.new_len <= 64 && !c.split_tokens;
+      const int32_t step_tok = n_new <= 2 ? 2 : (short_chunk ? 8 : tile_tok_for(pl.new_len));
       int32_t split = n_new <= 2 ? stream_split_for(c, pl.new_len) : tile_split_for(c, pl.new_len);
       // A short chunk on an empty history (an action chunk, Sec. 3.2) is cut into single 32-key
       // steps: its tiles start last (their keys are this step's new rows) and would otherwise
       // be the workgroups the launch ends with.  Depends on the item alone, like every split.
-      if (n_new > 2 && pl.old_len == 0 && pl.new_len <= 64 && !c.split_tokens) split = 32;
+      if (short_chunk) split = 32;
       for (int32_t t0 = 0; t0 < n_new; t0 += step_tok) {
         const int32_t n = std::min(step_tok, n_new - t0);
         const int32_t tok_off = (int32_t)toks.size();

@@ -190,9 +190,9 @@ def test_work_list_of_tiny_config():
             dec = [r for r in work if r[5] != 0x3fffffff]
             assert len(dec) == 1 and dec[0][5] == 4 and (dec[0][3], dec[0][4]) == (0, 5)
             assert dec[0][7] == 0
-            # action chunk: tiles of 4 + 4 + 2 tokens over its 10 own keys
+            # action chunk (short, on an empty history): tiles of 8 + 2 tokens over its 10 own keys
             act = [r for r in work if r[5] == 0x3fffffff and r[4] == 10]
-            assert sorted(int(r[1]) for r in act) == [2, 4, 4] and all(r[7] == 1 for r in act)
+            assert sorted(int(r[1]) for r in act) == [2, 8] and all(r[7] == 1 for r in act)
     assert len(seen) == 1
     assert seen[0][0] == 11 * 2            # one prefix partial + one own partial per token
 
